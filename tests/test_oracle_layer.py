@@ -1,0 +1,259 @@
+"""Pins for the oracle's forward and backward values (CPU only).
+
+Independent checks: a textbook dense FFN (the E=1, k=1, unlimited-capacity case),
+a per-token scalar-loop evaluation of the definition, automatic differentiation
+of the forward definition, central finite differences, partition independence
+(Section III-B), permutation identities of dispatch/combine, and the closed
+forms of the paper's memory model (Eq. 1-6).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_22175_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _inputs(T, M, H, E, k, cf, seed=0, x_std=1.0, w_std=0.3, **kw):
+    s = synth.custom_shape(T, M, H, E, k, cf, x_std=x_std, w_std=w_std, **kw)
+    return s, synth.make_inputs(s, seed=seed)
+
+
+# ---------- activation ----------------------------------------------------------
+
+def test_gelu_and_its_derivative(oracle):
+    z = np.linspace(-6, 6, 241)
+    ref = np.array([0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in z])
+    np.testing.assert_allclose(oracle.gelu(z), ref, atol=1e-15)
+    h = 1e-5
+    fd = (oracle.gelu(z + h) - oracle.gelu(z - h)) / (2 * h)
+    np.testing.assert_allclose(oracle.gelu_grad(z), fd, atol=1e-9)
+    assert oracle.gelu(np.array([0.0]))[0] == 0.0 and abs(oracle.gelu_grad(np.array([0.0]))[0] - 0.5) < 1e-15
+    # known value: gelu(1) = Phi(1) = 0.841344746...
+    assert abs(oracle.gelu(np.array([1.0]))[0] - 0.8413447460685429) < 1e-15
+
+
+# ---------- dense special case --------------------------------------------------
+
+def test_one_expert_unlimited_capacity_is_a_dense_ffn(oracle):
+    s, d = _inputs(40, 64, 48, 1, 1, 1.0, seed=1)
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], 1, 1.0, 1)
+    x = torch.tensor(d["x"], dtype=torch.float64, requires_grad=True)
+    W1 = torch.tensor(d["W1"][0], dtype=torch.float64, requires_grad=True)
+    W2 = torch.tensor(d["W2"][0], dtype=torch.float64, requires_grad=True)
+    y = torch.nn.functional.gelu(x @ W1) @ W2            # textbook FFN, erf GeLU
+    y.backward(torch.tensor(d["dy"], dtype=torch.float64))
+    np.testing.assert_allclose(r["y"], y.detach().numpy(), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(r["dx"], x.grad.numpy(), rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(r["dW1"][0], W1.grad.numpy(), rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(r["dW2"][0], W2.grad.numpy(), rtol=1e-11, atol=1e-13)
+    assert np.all(r["dWg"] == 0.0)                        # softmax over one expert is constant
+    assert np.all(r["w"] == 1.0) and np.all(r["slot"] == np.arange(40)[:, None])
+
+
+# ---------- forward against a scalar-loop evaluation ----------------------------
+
+def _forward_scalar(d, idx, w, slot):
+    T, M = d["x"].shape
+    y = np.zeros((T, M))
+    for t in range(T):
+        for j in range(idx.shape[1]):
+            if slot[t, j] < 0:
+                continue
+            e = idx[t, j]
+            z = [sum(float(d["x"][t, m]) * float(d["W1"][e, m, h]) for m in range(M))
+                 for h in range(d["W1"].shape[2])]
+            a = [0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in z]
+            for m in range(M):
+                y[t, m] += w[t, j] * sum(a[h] * float(d["W2"][e, h, m]) for h in range(len(a)))
+    return y
+
+
+def test_forward_matches_scalar_loops_with_drops(oracle):
+    s, d = _inputs(24, 8, 6, 3, 2, 0.75, seed=2)
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], 2, 0.75, 2)
+    assert (r["slot"] < 0).any()
+    y = _forward_scalar(d, r["idx"], r["w"], r["slot"])
+    np.testing.assert_allclose(r["y"], y, rtol=1e-12, atol=1e-15)
+
+
+# ---------- backward against automatic differentiation --------------------------
+
+def _torch_layer(d, idx, slot, k):
+    """Forward definition in torch (float64) with routing held constant."""
+    x = torch.tensor(d["x"], dtype=torch.float64, requires_grad=True)
+    Wg = torch.tensor(d["Wg"], dtype=torch.float64, requires_grad=True)
+    W1 = torch.tensor(d["W1"], dtype=torch.float64, requires_grad=True)
+    W2 = torch.tensor(d["W2"], dtype=torch.float64, requires_grad=True)
+    logits = x @ Wg
+    if "gate_bias" in d:
+        logits = logits + torch.tensor(d["gate_bias"], dtype=torch.float64)
+    p = torch.softmax(logits, dim=1)
+    y = torch.zeros_like(x)
+    rows = []
+    for t in range(x.shape[0]):
+        acc = torch.zeros(x.shape[1], dtype=torch.float64)
+        for j in range(k):
+            if slot[t, j] < 0:
+                continue
+            e = int(idx[t, j])
+            acc = acc + p[t, e] * (torch.nn.functional.gelu(x[t] @ W1[e]) @ W2[e])
+        rows.append(acc)
+    y = torch.stack(rows)
+    return x, Wg, W1, W2, y
+
+
+@pytest.mark.parametrize("T,M,H,E,k,cf,n,bias", [(16, 64, 16, 4, 2, 1.0, 1, False),
+                                                  (24, 8, 12, 3, 2, 0.75, 2, False),
+                                                  (32, 16, 8, 4, 1, 0.5, 2, True),
+                                                  (12, 8, 8, 3, 3, 1.0, 1, False)])
+def test_backward_matches_autograd_of_the_forward_definition(oracle, T, M, H, E, k, cf, n, bias):
+    kw = dict(zipf_s=1.2, zipf_tau=1.0) if bias else {}
+    s, d = _inputs(T, M, H, E, k, cf, seed=T, **kw)
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], k, cf, n, gate_bias=d.get("gate_bias"))
+    x, Wg, W1, W2, y = _torch_layer(d, r["idx"], r["slot"], k)
+    y.backward(torch.tensor(d["dy"], dtype=torch.float64))
+    yr = y.detach().numpy()
+    assert np.abs(r["y"] - yr).max() <= 1e-6 * np.abs(yr).max()      # oracle logits are float32
+    for name, g in (("dx", x.grad), ("dWg", Wg.grad), ("dW1", W1.grad), ("dW2", W2.grad)):
+        ref = g.numpy()
+        assert np.abs(r[name] - ref).max() <= 1e-6 * np.abs(ref).max() + 1e-12, name
+
+
+def test_backward_matches_central_finite_differences(oracle):
+    T, M, H, E, k = 8, 64, 16, 4, 2
+    s, d = _inputs(T, M, H, E, k, 1.0, seed=11)
+    base = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], k, 1.0, 1)
+    dyd = d["dy"].astype(np.float64)
+
+    def loss(dd):
+        # float64 forward with routing frozen at the unperturbed decision
+        x = dd["x"].astype(np.float64)
+        p = oracle.softmax_rows(x @ dd["Wg"].astype(np.float64))
+        tot = 0.0
+        for t in range(T):
+            for j in range(k):
+                if base["slot"][t, j] < 0:
+                    continue
+                e = int(base["idx"][t, j])
+                o = oracle.gelu(x[t] @ dd["W1"][e].astype(np.float64)) @ dd["W2"][e].astype(np.float64)
+                tot += p[t, e] * float(dyd[t] @ o)
+        return tot
+
+    g = np.random.default_rng(0)
+    for name, grad in (("x", base["dx"]), ("Wg", base["dWg"]), ("W1", base["dW1"]), ("W2", base["dW2"])):
+        arr = d[name].astype(np.float64)
+        for _ in range(6):
+            pos = tuple(g.integers(0, n_) for n_ in arr.shape)
+            eps = 1e-5
+            dd = {k_: v.astype(np.float64) for k_, v in d.items()}
+            dd[name] = arr.copy(); dd[name][pos] += eps
+            lp = loss(dd)
+            dd[name] = arr.copy(); dd[name][pos] -= eps
+            lm = loss(dd)
+            fd = (lp - lm) / (2 * eps)
+            scale = np.abs(grad).max()
+            # float32 logits in the oracle vs float64 here: agreement to ~1e-6 of the tensor's scale
+            assert abs(fd - grad[pos]) <= 2e-6 * scale + 1e-9, (name, pos, fd, grad[pos])
+
+
+# ---------- drops, partitions, permutations -------------------------------------
+
+def test_fully_dropped_tokens_give_exact_zero(oracle):
+    s, d = _inputs(64, 16, 8, 2, 1, 0.25, seed=3)
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], 1, 0.25, 1)
+    dropped = (r["slot"] < 0).all(axis=1)
+    assert dropped.any() and not dropped.all()
+    assert np.all(r["y"][dropped] == 0.0)
+    assert np.all(r["dx"][dropped] == 0.0)
+    assert np.all(r["dw"][r["slot"] < 0] == 0.0)
+    assert np.abs(r["y"][~dropped]).max() > 0
+
+
+def test_partitions_are_independent(oracle):
+    """Running n partitions equals n separate runs on the token slices, weight
+    gradients summed; with capacity that cannot overflow the result is the same for every n."""
+    s, d = _inputs(48, 16, 12, 4, 2, 0.75, seed=4)
+    n = 3
+    whole = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], 2, 0.75, n)
+    T_p = 48 // n
+    acc = {k_: 0.0 for k_ in ("dWg", "dW1", "dW2")}
+    for p in range(n):
+        sl = slice(p * T_p, (p + 1) * T_p)
+        part = oracle.layer_step(d["x"][sl], d["Wg"], d["W1"], d["W2"], d["dy"][sl], 2, 0.75, 1)
+        assert part["C_p"] == whole["C_p"]
+        assert np.array_equal(part["slot"], whole["slot"][sl])
+        assert np.array_equal(part["counts"][0], whole["counts"][p])
+        np.testing.assert_allclose(part["y"], whole["y"][sl], rtol=1e-13, atol=1e-16)
+        np.testing.assert_allclose(part["dx"], whole["dx"][sl], rtol=1e-13, atol=1e-16)
+        for k_ in acc:
+            acc[k_] = acc[k_] + part[k_]
+    for k_ in acc:
+        np.testing.assert_allclose(acc[k_], whole[k_], rtol=1e-12, atol=1e-15)
+    # no drops possible (cf >= E/k): identical values for every n
+    ref = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], 2, 2.0, 1)
+    for n2 in (2, 4):
+        r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], 2, 2.0, n2)
+        assert not (r["slot"] < 0).any()
+        for k_ in ("y", "dx", "dWg", "dW1", "dW2"):
+            np.testing.assert_allclose(r[k_], ref[k_], rtol=1e-11, atol=1e-14)
+
+
+def test_dispatch_and_combine_are_inverse_permutations(oracle):
+    s, d = _inputs(32, 8, 8, 4, 1, 4.0, seed=5)
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], 1, 4.0, 1, keep_intermediates=True)
+    assert not (r["slot"] < 0).any()
+    C_p = r["C_p"]
+    DI = np.zeros((4 * C_p, 8))
+    for (p, e), it in r["inter"].items():
+        DI[e * C_p:e * C_p + len(it["tokens"])] = it["DI"]
+    # combine with unit weights undoes the dispatch
+    back = DI[r["slot"][:, 0]]
+    assert np.array_equal(back, d["x"].astype(np.float64))
+    # gradient rows sent back to the experts are the weighted upstream rows, in slot order
+    for (p, e), it in r["inter"].items():
+        np.testing.assert_array_equal(it["dO"], r["w"][it["tokens"], it["choice"]][:, None] * d["dy"][it["tokens"]].astype(np.float64))
+
+
+# ---------- sampled evaluation --------------------------------------------------
+
+def test_sampled_evaluation_equals_the_full_one(oracle):
+    s, d = _inputs(96, 16, 24, 4, 2, 0.8, seed=6)
+    n = 2
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], 2, 0.8, n)
+    toks = [0, 5, 47, 48, 95] + list(np.nonzero((r["slot"] < 0).any(axis=1))[0][:3])
+    sm = oracle.sampled_tokens(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], r, toks)
+    np.testing.assert_allclose(sm["y"], r["y"][toks], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(sm["dx"], r["dx"][toks], rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(sm["dw"], r["dw"][toks], rtol=1e-12, atol=1e-15)
+    for e in range(4):
+        a, b = oracle.sampled_weight_grads(d["x"], d["W1"], d["W2"], d["dy"], r, n, r["C_p"], e, [0, 7, 23], [1, 15])
+        np.testing.assert_allclose(a, r["dW1"][e][:, [0, 7, 23]], rtol=1e-11, atol=1e-14)
+        np.testing.assert_allclose(b, r["dW2"][e][:, [1, 15]], rtol=1e-11, atol=1e-14)
+
+
+# ---------- memory model --------------------------------------------------------
+
+def test_memory_saving_ratio_matches_hand_evaluated_values(oracle):
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "eq6_phi.txt")) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 6
+    for M, H, E, B, n, phi in rows:
+        got = oracle.paper_memory_model(int(B), int(M), int(H), int(E), int(n))["phi"]
+        assert abs(got - float(phi)) < 5e-5
+
+
+def test_memory_model_closed_forms(oracle):
+    m = oracle.paper_memory_model(B=1000, M=10, H=40, E=4, n=4)
+    assert m["M_ms"] == 4 * (40 + 800) and m["M_act"] == 40000 + 40000 and m["M_buf"] == 10000 + 40000
+    assert m["delta"] == 1000 * (20 * 2 / 4 + 40 * 3 / 4)
+    # n = 2: double-buffered T_DI/T_DO save nothing, T_M halves; n = 1 has no saving to give
+    assert oracle.paper_memory_model(1000, 10, 40, 4, 2)["delta"] == 1000 * 20
+    # workspace bookkeeping agrees with Eq. 5 when rows stand in for tokens
+    R_p, n, M, H = 128, 4, 10, 40
+    full = oracle.workspace_model(R_p, n, M, H, 0)
+    assert full - oracle.workspace_model(R_p, n, M, H, 2) == oracle.paper_memory_model(R_p * n, M, H, 1, n)["delta"]
+    assert full - oracle.workspace_model(R_p, n, M, H, 1) == R_p * n * 2 * M * (n - 2) / n
