@@ -1,0 +1,201 @@
+/*
+ * C ABI of the MI355X (gfx950) MoE-layer hot path.
+ *
+ * One GPU's share of a Mixture-of-Experts layer's training step: gate ->
+ * capacity-bounded dispatch -> per-expert FFN (linear, GeLU, linear) ->
+ * weighted combine, forward and backward, run as n micro-batch partitions on
+ * HIP streams with optional sharing of partition buffers and recomputation of
+ * the middle activation (MPipeMoE, Sections II-A, II-B2, III-B, III-D).
+ *
+ * Conventions for every call unless stated otherwise
+ *   - every pointer is a DEVICE pointer owned by the caller; the library never
+ *     allocates, frees or keeps device memory (the config and the size queries
+ *     are host memory);
+ *   - tensors are dense, row-major, 16-byte aligned; element type `dtype` is
+ *     MOE_F32 (float) or MOE_BF16 (bfloat16 bit patterns) for x, dy, y, dx, Wg,
+ *     W1, W2 and all activation buffers; logits, combine weights and weight
+ *     gradients are always float; indices are int32;
+ *   - `stream` is a hipStream_t passed as void*; calls are asynchronous and
+ *     stream-ordered;
+ *   - the return value is a moe_status; nothing throws or aborts.
+ *       MOE_ERR_NULL        a required pointer is NULL
+ *       MOE_ERR_SHAPE       non-positive dimension, k > E, T % n != 0, cf <= 0,
+ *                           partition index out of range
+ *       MOE_ERR_UNSUPPORTED E > 64, k > 8, M % 8 != 0, H % 8 != 0
+ *       MOE_ERR_WORKSPACE   workspace smaller than moe_workspace_bytes()
+ *       MOE_ERR_HIP         a HIP call or kernel launch failed
+ *   - notation: T tokens, M model dim, H expert hidden dim, E local experts,
+ *     k experts per token, n partitions, T_p = T/n, C_p = rows per expert per
+ *     partition, R_p = E*C_p rows of one partition's expert-contiguous buffers.
+ *   - rows of a partition buffer at or beyond counts[p][e] inside expert e's
+ *     C_p-row segment are padding: never read as data, contents unspecified.
+ */
+#ifndef MOE_H
+#define MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0, MOE_ERR_NULL = 1, MOE_ERR_SHAPE = 2, MOE_ERR_UNSUPPORTED = 3,
+    MOE_ERR_WORKSPACE = 4, MOE_ERR_HIP = 5
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+/* Memory-reuse modes (Section III-D, Table II).
+ *   NONE      every partition's T_DI, T_M, T_DO is kept for backward (row "none").
+ *   BUFFERS   T_DI and T_DO live in two partition-sized buffers each; T_DI is
+ *             re-dispatched from T_I in backward; T_M is kept whole.
+ *   RECOMPUTE as BUFFERS, and T_M lives in one partition-sized buffer and is
+ *             recomputed from T_DI in backward (strategy S4 with the
+ *             re-communication read as a local re-dispatch). */
+typedef enum { MOE_REUSE_NONE = 0, MOE_REUSE_BUFFERS = 1, MOE_REUSE_RECOMPUTE = 2 } moe_reuse;
+
+typedef struct {
+    int32_t T, M, H, E, k;
+    float capacity_factor;
+    int32_t n_partitions;
+    int32_t dtype;   /* moe_dtype */
+    int32_t reuse;   /* moe_reuse */
+} moe_config;
+
+/* Host only.  C_p = ceil(capacity_factor * k * (T / n) / E), evaluated in double
+ * from the float capacity_factor.  (The paper has no capacity; each micro-batch
+ * of Section III-B is treated as an independent MoE call, so the bound is per
+ * partition and buffers are exactly 1/n of the whole.) */
+moe_status moe_capacity(const moe_config* cfg, int32_t* C_p);
+
+/* Host only.  Bytes of the workspace moe_layer_step needs for cfg, and how they
+ * split: `saved` = activations kept from forward for backward (T_DI, T_M, T_DO
+ * in the sense of Eq. 2 / Eq. 4), `temp` = forward/backward temporaries (Eq. 3),
+ * `routing` = slot weights, gate gradients, partial sums.  Any output pointer
+ * may be NULL. */
+moe_status moe_workspace_bytes(const moe_config* cfg, size_t* total, size_t* saved,
+                               size_t* temp, size_t* routing);
+
+/* Gate (Sections II-B2, IV-A): logits = x Wg (+ gate_bias) in float with a fixed
+ * summation order (element d goes to accumulator (d/8) mod 64, fused
+ * multiply-adds in ascending d, then pairwise folding with offsets 32..1, bias
+ * added last); softmax over all E; the k largest logits, ties to the lower
+ * index, NaN ordered as -inf; topk_w are the chosen probabilities.
+ *   x [T,M], Wg [M,E] in dtype; gate_bias [E] float, may be NULL;
+ *   logits [T,E] float out; topk_idx [T,k] int32 out; topk_w [T,k] float out. */
+moe_status moe_route(const moe_config* cfg, const void* x, const void* Wg, const float* gate_bias,
+                     float* logits, int32_t* topk_idx, float* topk_w, void* stream);
+
+/* Capacity-bounded slot assignment for all n partitions.  Inside a partition,
+ * positions are granted choice-major (all first choices in token order, then
+ * second choices, ...); an assignment whose position reaches C_p is dropped.
+ *   slot [T,k] int32 out: partition-local row e*C_p + pos, or -1 if dropped;
+ *   counts [n,E] int32 out: kept rows per expert;
+ *   slot_w [n*R_p] float out, may be NULL: combine weight of the assignment that
+ *   owns each kept row (padding rows are not written);
+ *   scratch: at least moe_slot_scratch_bytes(cfg) bytes. */
+moe_status moe_assign_slots(const moe_config* cfg, const int32_t* topk_idx, const float* topk_w,
+                            int32_t* slot, int32_t* counts, float* slot_w,
+                            void* scratch, void* stream);
+moe_status moe_slot_scratch_bytes(const moe_config* cfg, size_t* bytes);
+
+/* Dispatch S of partition `part` (Fig. 1: T_I -> T_DI; on one GPU the All-to-All
+ * is a local permutation): DI[slot[t,j]] = src[t] for every kept (t, j) of the
+ * partition's tokens.  src [T,M] (x, or dy in backward); DI [R_p,M] out.
+ * If dO_saved and dw are non-NULL also dw[t,j] = <src[t], dO_saved[slot[t,j]]>
+ * (0 if dropped): the combine-weight gradient when T_DO was kept. */
+moe_status moe_dispatch(const moe_config* cfg, int32_t part, const void* src, const int32_t* slot,
+                        void* DI, const void* dO_saved, float* dw, void* stream);
+
+/* Expert FFN forward of one partition (Section II-B2: T_DI -> T_M -> T_DO).
+ * For each expert e and its counts[part][e] rows: Z = DI W1[e]; A = gelu(Z)
+ * (erf form); DO = A W2[e].  bf16 runs on MFMA with float accumulation.
+ *   DI [R_p,M]; counts [n,E]; W1 [E,M,H]; W2 [E,H,M];
+ *   Z [R_p,H] out, may be NULL when the pre-activation is not kept;
+ *   A [R_p,H] scratch (activated rows, dead after the call); DO [R_p,M] out. */
+moe_status moe_expert_ffn_fwd(const moe_config* cfg, int32_t part, const void* DI, const int32_t* counts,
+                              const void* W1, const void* W2, void* Z, void* A, void* DO, void* stream);
+
+/* Expert FFN backward of one partition ("symmetric", Section III-B; Table II's
+ * 4 GEMMs, 5 with recomputation).  dDO holds the UNWEIGHTED upstream rows
+ * (dispatch of dy); the combine weight of each row is applied here:
+ *   [recompute != 0: Z = DI W1[e] first]
+ *   G = dDO W2[e]^T;  dw_part[row, c] = partial sums over column block c of
+ *   <gelu(Z_row), G_row> (their sum over c is d loss / d weight of the row);
+ *   dZ = slot_w * G * gelu'(Z);  Z is overwritten with slot_w * gelu(Z);
+ *   dW2[e] += (slot_w gelu(Z))^T dDO;  dDI = dZ W1[e]^T;  dW1[e] += DI^T dZ.
+ *   Z [R_p,H] in/out (input ignored when recompute); dZ [R_p,H] scratch;
+ *   dDI [R_p,M] out; dW1 [E,M,H], dW2 [E,H,M] float, accumulated into;
+ *   dw_part [R_p, moe_dw_parts(cfg)] float out, may be NULL. */
+moe_status moe_expert_ffn_bwd(const moe_config* cfg, int32_t part, int32_t recompute,
+                              const void* DI, void* Z, const void* dDO, const int32_t* counts,
+                              const float* slot_w, const void* W1, const void* W2,
+                              void* dZ, void* dDI, float* dW1, float* dW2, float* dw_part, void* stream);
+moe_status moe_dw_parts(const moe_config* cfg, int32_t* parts);
+
+/* Combine R of partition `part` (Fig. 1: T_DO -> T_O): for the partition's tokens
+ * y[t] = sum over kept j of topk_w[t,j] * DO[slot[t,j]], float accumulation in
+ * ascending j; exactly zero when every choice was dropped.  y [T,M] out. */
+moe_status moe_combine(const moe_config* cfg, int32_t part, const void* DO, const int32_t* slot,
+                       const float* topk_w, void* y, void* stream);
+
+/* Gate backward of partition `part`: dL = softmax Jacobian applied to the
+ * combine-weight gradients, dWg += x^T dL (two-stage, fixed order).
+ *   dw [T,k] float (used when dw_part is NULL) or dw_part [R_p, parts] summed in
+ *   ascending c; dL [T,E] float out; scratch: moe_gate_scratch_bytes(cfg). */
+moe_status moe_gate_bwd(const moe_config* cfg, int32_t part, const void* x, const float* logits,
+                        const int32_t* topk_idx, const int32_t* slot, const float* dw,
+                        const float* dw_part, float* dL, float* dWg, void* scratch, void* stream);
+moe_status moe_gate_scratch_bytes(const moe_config* cfg, size_t* bytes);
+
+/* Dispatch backward S' of partition `part`:
+ * dx[t] = sum over kept j of dDI[slot[t,j]] + dL[t,:] Wg^T.   dx [T,M] out. */
+moe_status moe_dispatch_bwd(const moe_config* cfg, int32_t part, const void* dDI, const int32_t* slot,
+                            const float* dL, const void* Wg, void* dx, void* stream);
+
+/* One whole training step of the layer: route, then for each partition
+ * S -> C -> R pipelined over two streams (permutations on streams[0], GEMMs on
+ * streams[1]; Section III-B), then the backward pass in the same fashion, under
+ * cfg->reuse (Section III-D).  Forks from streams[0] and joins back to it: the
+ * caller synchronises streams[0] only.  n_streams must be >= 2 (both may be the
+ * same stream, which serialises the schedule).
+ *   x, dy [T,M]; y, dx [T,M] out; dWg [M,E], dW1 [E,M,H], dW2 [E,H,M] float,
+ *   accumulated into (caller zeroes); logits [T,E], topk_idx, topk_w, slot
+ *   [T,k], counts [n,E] out; workspace of moe_workspace_bytes(cfg). */
+moe_status moe_layer_step(const moe_config* cfg, const void* x, const void* dy,
+                          const void* Wg, const float* gate_bias, const void* W1, const void* W2,
+                          void* y, void* dx, float* dWg, float* dW1, float* dW2,
+                          float* logits, int32_t* topk_idx, float* topk_w, int32_t* slot, int32_t* counts,
+                          void* workspace, size_t workspace_bytes,
+                          void* const* streams, int32_t n_streams);
+
+/* Forward half / backward half of moe_layer_step, for callers that run other
+ * work between them.  Same arguments and workspace; backward reads what forward
+ * left in the workspace and in the routing outputs. */
+moe_status moe_layer_forward(const moe_config* cfg, const void* x,
+                             const void* Wg, const float* gate_bias, const void* W1, const void* W2,
+                             void* y, float* logits, int32_t* topk_idx, float* topk_w,
+                             int32_t* slot, int32_t* counts,
+                             void* workspace, size_t workspace_bytes,
+                             void* const* streams, int32_t n_streams);
+moe_status moe_layer_backward(const moe_config* cfg, const void* x, const void* dy,
+                              const void* Wg, const void* W1, const void* W2,
+                              void* dx, float* dWg, float* dW1, float* dW2,
+                              const float* logits, const int32_t* topk_idx, const float* topk_w,
+                              const int32_t* slot, const int32_t* counts,
+                              void* workspace, size_t workspace_bytes,
+                              void* const* streams, int32_t n_streams);
+
+/* Counters of kernels launched by this process since the last reset, by class:
+ * out[0] GEMM launches, out[1] permutation launches (dispatch, combine,
+ * dispatch-backward), out[2] everything else.  Host only. */
+moe_status moe_launch_counts(int64_t out[3], int32_t reset);
+
+const char* moe_status_string(moe_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H */

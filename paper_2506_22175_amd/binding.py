@@ -1,0 +1,209 @@
+"""Thin ctypes binding of libmoe_hip.so: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point in
+include/moe.h; tensors are torch tensors on the GPU (used here only as device
+memory), streams are torch.cuda.Stream objects or raw integers.  A non-zero
+status raises MoEError.  There is no CPU fallback: if the HIP library is not
+built, importing this module's functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
+
+MOE_F32, MOE_BF16 = 0, 1
+MOE_REUSE_NONE, MOE_REUSE_BUFFERS, MOE_REUSE_RECOMPUTE = 0, 1, 2
+
+EXPORTS = [
+    "moe_capacity", "moe_workspace_bytes", "moe_route", "moe_assign_slots", "moe_slot_scratch_bytes",
+    "moe_dispatch", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_dw_parts", "moe_combine",
+    "moe_gate_bwd", "moe_gate_scratch_bytes", "moe_dispatch_bwd", "moe_layer_step",
+    "moe_layer_forward", "moe_layer_backward", "moe_launch_counts", "moe_status_string",
+]
+
+
+class MoEError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+class MoEConfig(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("M", ctypes.c_int32), ("H", ctypes.c_int32), ("E", ctypes.c_int32),
+                ("k", ctypes.c_int32), ("capacity_factor", ctypes.c_float), ("n_partitions", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("reuse", ctypes.c_int32)]
+
+
+def make_config(T, M, H, E, k, capacity_factor, n_partitions=1, dtype=MOE_BF16, reuse=MOE_REUSE_NONE) -> MoEConfig:
+    return MoEConfig(int(T), int(M), int(H), int(E), int(k), float(capacity_factor), int(n_partitions),
+                     int(dtype), int(reuse))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_2506_22175_amd.build` "
+                               "(there is no fallback path)")
+        _lib = ctypes.CDLL(LIB_PATH)
+        for name in EXPORTS:
+            fn = getattr(_lib, name)
+            fn.restype = ctypes.c_char_p if name == "moe_status_string" else ctypes.c_int
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().moe_status_string(ctypes.c_int(status)).decode()
+
+
+def _p(t) -> ctypes.c_void_p:
+    """Device (or host) pointer of a tensor, an int, or None."""
+    if t is None:
+        return ctypes.c_void_p(0)
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _s(stream) -> ctypes.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise MoEError(status, where)
+
+
+def _cfg(cfg: MoEConfig):
+    return ctypes.byref(cfg)
+
+
+# ---- host-only queries -----------------------------------------------------------
+
+def moe_capacity(cfg: MoEConfig) -> int:
+    out = ctypes.c_int32(0)
+    _check(lib().moe_capacity(_cfg(cfg), ctypes.byref(out)), "moe_capacity")
+    return out.value
+
+
+def moe_workspace_bytes(cfg: MoEConfig):
+    """(total, saved, temp, routing) bytes."""
+    v = [ctypes.c_size_t(0) for _ in range(4)]
+    _check(lib().moe_workspace_bytes(_cfg(cfg), *[ctypes.byref(x) for x in v]), "moe_workspace_bytes")
+    return tuple(x.value for x in v)
+
+
+def moe_slot_scratch_bytes(cfg: MoEConfig) -> int:
+    v = ctypes.c_size_t(0)
+    _check(lib().moe_slot_scratch_bytes(_cfg(cfg), ctypes.byref(v)), "moe_slot_scratch_bytes")
+    return v.value
+
+
+def moe_gate_scratch_bytes(cfg: MoEConfig) -> int:
+    v = ctypes.c_size_t(0)
+    _check(lib().moe_gate_scratch_bytes(_cfg(cfg), ctypes.byref(v)), "moe_gate_scratch_bytes")
+    return v.value
+
+
+def moe_dw_parts(cfg: MoEConfig) -> int:
+    v = ctypes.c_int32(0)
+    _check(lib().moe_dw_parts(_cfg(cfg), ctypes.byref(v)), "moe_dw_parts")
+    return v.value
+
+
+def moe_launch_counts(reset: bool = False):
+    arr = (ctypes.c_int64 * 3)()
+    _check(lib().moe_launch_counts(arr, ctypes.c_int32(1 if reset else 0)), "moe_launch_counts")
+    return tuple(arr)
+
+
+# ---- device calls ----------------------------------------------------------------
+
+def moe_route(cfg, x, Wg, gate_bias, logits, topk_idx, topk_w, stream=None):
+    _check(lib().moe_route(_cfg(cfg), _p(x), _p(Wg), _p(gate_bias), _p(logits), _p(topk_idx), _p(topk_w),
+                           _s(stream)), "moe_route")
+
+
+def moe_assign_slots(cfg, topk_idx, topk_w, slot, counts, slot_w, scratch, stream=None):
+    _check(lib().moe_assign_slots(_cfg(cfg), _p(topk_idx), _p(topk_w), _p(slot), _p(counts), _p(slot_w),
+                                  _p(scratch), _s(stream)), "moe_assign_slots")
+
+
+def moe_dispatch(cfg, part, src, slot, DI, dO_saved=None, dw=None, stream=None):
+    _check(lib().moe_dispatch(_cfg(cfg), ctypes.c_int32(part), _p(src), _p(slot), _p(DI), _p(dO_saved), _p(dw),
+                              _s(stream)), "moe_dispatch")
+
+
+def moe_expert_ffn_fwd(cfg, part, DI, counts, W1, W2, Z, A, DO, stream=None):
+    _check(lib().moe_expert_ffn_fwd(_cfg(cfg), ctypes.c_int32(part), _p(DI), _p(counts), _p(W1), _p(W2),
+                                    _p(Z), _p(A), _p(DO), _s(stream)), "moe_expert_ffn_fwd")
+
+
+def moe_expert_ffn_bwd(cfg, part, recompute, DI, Z, dDO, counts, slot_w, W1, W2, dZ, dDI, dW1, dW2, dw_part,
+                       stream=None):
+    _check(lib().moe_expert_ffn_bwd(_cfg(cfg), ctypes.c_int32(part), ctypes.c_int32(int(recompute)), _p(DI),
+                                    _p(Z), _p(dDO), _p(counts), _p(slot_w), _p(W1), _p(W2), _p(dZ), _p(dDI),
+                                    _p(dW1), _p(dW2), _p(dw_part), _s(stream)), "moe_expert_ffn_bwd")
+
+
+def moe_combine(cfg, part, DO, slot, topk_w, y, stream=None):
+    _check(lib().moe_combine(_cfg(cfg), ctypes.c_int32(part), _p(DO), _p(slot), _p(topk_w), _p(y), _s(stream)),
+           "moe_combine")
+
+
+def moe_gate_bwd(cfg, part, x, logits, topk_idx, slot, dw, dw_part, dL, dWg, scratch, stream=None):
+    _check(lib().moe_gate_bwd(_cfg(cfg), ctypes.c_int32(part), _p(x), _p(logits), _p(topk_idx), _p(slot),
+                              _p(dw), _p(dw_part), _p(dL), _p(dWg), _p(scratch), _s(stream)), "moe_gate_bwd")
+
+
+def moe_dispatch_bwd(cfg, part, dDI, slot, dL, Wg, dx, stream=None):
+    _check(lib().moe_dispatch_bwd(_cfg(cfg), ctypes.c_int32(part), _p(dDI), _p(slot), _p(dL), _p(Wg), _p(dx),
+                                  _s(stream)), "moe_dispatch_bwd")
+
+
+def _streams(streams: Optional[Sequence]):
+    import torch
+    if streams is None:
+        cur = torch.cuda.current_stream()
+        streams = [cur, cur]
+    arr = (ctypes.c_void_p * len(streams))(*[_s(s).value for s in streams])
+    return arr, ctypes.c_int32(len(streams))
+
+
+def moe_layer_step(cfg, x, dy, Wg, gate_bias, W1, W2, y, dx, dWg, dW1, dW2, logits, topk_idx, topk_w, slot,
+                   counts, workspace, streams=None):
+    arr, n = _streams(streams)
+    _check(lib().moe_layer_step(_cfg(cfg), _p(x), _p(dy), _p(Wg), _p(gate_bias), _p(W1), _p(W2), _p(y), _p(dx),
+                                _p(dWg), _p(dW1), _p(dW2), _p(logits), _p(topk_idx), _p(topk_w), _p(slot),
+                                _p(counts), _p(workspace), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+                                arr, n), "moe_layer_step")
+
+
+def moe_layer_forward(cfg, x, Wg, gate_bias, W1, W2, y, logits, topk_idx, topk_w, slot, counts, workspace,
+                      streams=None):
+    arr, n = _streams(streams)
+    _check(lib().moe_layer_forward(_cfg(cfg), _p(x), _p(Wg), _p(gate_bias), _p(W1), _p(W2), _p(y), _p(logits),
+                                   _p(topk_idx), _p(topk_w), _p(slot), _p(counts), _p(workspace),
+                                   ctypes.c_size_t(workspace.numel() * workspace.element_size()), arr, n),
+           "moe_layer_forward")
+
+
+def moe_layer_backward(cfg, x, dy, Wg, W1, W2, dx, dWg, dW1, dW2, logits, topk_idx, topk_w, slot, counts,
+                       workspace, streams=None):
+    arr, n = _streams(streams)
+    _check(lib().moe_layer_backward(_cfg(cfg), _p(x), _p(dy), _p(Wg), _p(W1), _p(W2), _p(dx), _p(dWg), _p(dW1),
+                                    _p(dW2), _p(logits), _p(topk_idx), _p(topk_w), _p(slot), _p(counts),
+                                    _p(workspace), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+                                    arr, n), "moe_layer_backward")

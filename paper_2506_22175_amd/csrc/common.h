@@ -1,0 +1,144 @@
+// Shared declarations of the gfx950 MoE-layer library (internal; the public
+// interface is include/moe.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "moe.h"
+
+namespace moe {
+
+typedef unsigned short bf16_t;   // bfloat16 bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+    return __uint_as_float(((unsigned)v) << 16);
+}
+// round to nearest, ties to even (v_cvt_pk_bf16_f32 on gfx950)
+typedef __bf16 hw_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float hw_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    return __builtin_bit_cast(bf16_t, (__bf16)f);
+}
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+    hw_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, hw_bf16x2));
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float ld(const float* p) { return *p; }
+    static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    static __device__ __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// eight consecutive elements <-> eight floats (16 bytes of bf16, 32 bytes of float)
+template <typename T> struct Vec8;
+template <> struct Vec8<bf16_t> {
+    static __device__ __forceinline__ void load(const bf16_t* p, float* o) {
+        uint4 u = *reinterpret_cast<const uint4*>(p);
+        unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o[2 * i] = __uint_as_float(w[i] << 16);
+            o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(bf16_t* p, const float* v) {
+        uint4 u;
+        u.x = pack_bf16x2(v[0], v[1]); u.y = pack_bf16x2(v[2], v[3]);
+        u.z = pack_bf16x2(v[4], v[5]); u.w = pack_bf16x2(v[6], v[7]);
+        *reinterpret_cast<uint4*>(p) = u;
+    }
+};
+template <> struct Vec8<float> {
+    static __device__ __forceinline__ void load(const float* p, float* o) {
+        float4 a = *reinterpret_cast<const float4*>(p);
+        float4 b = *reinterpret_cast<const float4*>(p + 4);
+        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+        o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+    }
+    static __device__ __forceinline__ void store(float* p, const float* v) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+};
+
+// exact GeLU (erf form) and its derivative
+__device__ __forceinline__ float gelu_f(float z) {
+    return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float gelu_grad_f(float z) {
+    float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
+    float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+    return cdf + z * pdf;
+}
+__device__ __forceinline__ void gelu_both_f(float z, float* g, float* dg) {
+    float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
+    float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+    *g = z * cdf;
+    *dg = cdf + z * pdf;
+}
+
+struct Dims {
+    int T, M, H, E, k, n, Tp, Cp, Rp;
+    int dtype, reuse;
+    size_t es;   // element size in bytes
+};
+
+// Validates cfg and fills Dims.  Host.
+moe_status make_dims(const moe_config* cfg, Dims* d);
+moe_status check_part(const Dims& d, int part);
+
+inline moe_status hip_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
+#define MOE_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP; } while (0)
+#define MOE_TRY(expr) do { moe_status _s = (expr); if (_s != MOE_OK) return _s; } while (0)
+
+enum LaunchClass { LC_GEMM = 0, LC_PERMUTE = 1, LC_OTHER = 2 };
+void count_launch(LaunchClass c, int n = 1);
+
+// ---- grouped GEMM interface (gemm_bf16.hip / gemm_f32.hip) -------------------
+// Three operand layouts, all per expert e with r = counts[e] valid rows:
+//   NN: C[r,N] = A[r,K] * B[K,N]         A rows K-contiguous, B rows N-contiguous
+//   NT: C[r,N] = A[r,K] * B[N,K]^T       both K-contiguous
+//   TN: C[Mo,N] (+)= A[r,Mo]^T * B[r,N]  reduction over the r valid rows
+enum GemmLayout { GEMM_NN = 0, GEMM_NT = 1, GEMM_TN = 2 };
+enum GemmEpilogue {
+    EPI_STORE = 0,      // C = acc                       (element type)
+    EPI_GELU = 1,       // Z = acc (optional), A = gelu(Z)
+    EPI_DGELU = 2,      // dZ = w*acc*gelu'(Z), Z <- w*gelu(Z), dw_part = <gelu(Z), acc>
+    EPI_ACCUM_F32 = 3   // C(float) += acc
+};
+
+struct GemmArgs {
+    const void* A; const void* B; void* C;
+    long long a_estride, b_estride, c_estride;   // elements between experts
+    int lda, ldb, ldc;
+    const int* counts;    // [E] valid rows of this partition
+    int E, Cp;            // experts, max rows per expert
+    int Mo;               // TN only: output rows
+    int N, K;             // K unused for TN (K = counts[e])
+    // epilogue operands
+    void* Z;              // EPI_GELU: optional pre-activation out; EPI_DGELU: in/out
+    int ldz;              // row stride of Z (elements); expert stride is Cp*ldz
+    const float* slot_w;  // EPI_DGELU: [E*Cp] row weights
+    float* dw_part;       // EPI_DGELU: [E*Cp, dw_parts] or NULL
+    int dw_parts;
+};
+
+moe_status gemm_bf16(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStream_t s);
+moe_status gemm_f32(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStream_t s);
+int gemm_bf16_dw_parts(int H);   // column blocks the DGELU epilogue reports per row
+int gemm_f32_dw_parts(int H);
+
+
+// ---- one partition's expert FFN (ffn.hip) ---------------------------------------
+moe_status ffn_fwd(const Dims& d, int part, const void* DI, const int* counts, const void* W1, const void* W2,
+                   void* Z, void* A, void* DO, hipStream_t s);
+moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void* Z, const void* dDO,
+                   const int* counts, const float* slot_w, const void* W1, const void* W2,
+                   void* dZ, void* dDI, float* dW1, float* dW2, float* dw_part, hipStream_t s);
+
+}  // namespace moe

@@ -1,0 +1,66 @@
+// Host-side helpers: configuration checks, capacity, launch counters.
+#include "common.h"
+#include <atomic>
+#include <cmath>
+
+namespace moe {
+
+moe_status make_dims(const moe_config* cfg, Dims* d) {
+    if (!cfg || !d) return MOE_ERR_NULL;
+    if (cfg->T <= 0 || cfg->M <= 0 || cfg->H <= 0 || cfg->E <= 0 || cfg->k <= 0) return MOE_ERR_SHAPE;
+    if (cfg->k > cfg->E) return MOE_ERR_SHAPE;
+    if (!(cfg->capacity_factor > 0.0f) || !std::isfinite(cfg->capacity_factor)) return MOE_ERR_SHAPE;
+    if (cfg->n_partitions <= 0 || cfg->T % cfg->n_partitions != 0) return MOE_ERR_SHAPE;
+    if (cfg->dtype != MOE_F32 && cfg->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+    if (cfg->reuse < MOE_REUSE_NONE || cfg->reuse > MOE_REUSE_RECOMPUTE) return MOE_ERR_UNSUPPORTED;
+    if (cfg->E > 64 || cfg->k > 8 || cfg->n_partitions > 64) return MOE_ERR_UNSUPPORTED;
+    if (cfg->M % 8 != 0 || cfg->H % 8 != 0) return MOE_ERR_UNSUPPORTED;
+    d->T = cfg->T; d->M = cfg->M; d->H = cfg->H; d->E = cfg->E; d->k = cfg->k;
+    d->n = cfg->n_partitions; d->Tp = cfg->T / cfg->n_partitions;
+    double c = std::ceil((double)cfg->capacity_factor * (double)((long long)cfg->k * d->Tp) / (double)cfg->E);
+    if (c < 1.0) c = 1.0;
+    if (c * (double)cfg->E > 2.0e9) return MOE_ERR_SHAPE;
+    d->Cp = (int)c;
+    d->Rp = d->Cp * d->E;
+    d->dtype = cfg->dtype; d->reuse = cfg->reuse;
+    d->es = cfg->dtype == MOE_F32 ? 4 : 2;
+    return MOE_OK;
+}
+
+moe_status check_part(const Dims& d, int part) {
+    return (part < 0 || part >= d.n) ? MOE_ERR_SHAPE : MOE_OK;
+}
+
+static std::atomic<long long> g_launches[3];
+void count_launch(LaunchClass c, int n) { g_launches[c].fetch_add(n, std::memory_order_relaxed); }
+
+}  // namespace moe
+
+extern "C" moe_status moe_capacity(const moe_config* cfg, int32_t* C_p) {
+    moe::Dims d;
+    MOE_TRY(moe::make_dims(cfg, &d));
+    if (!C_p) return MOE_ERR_NULL;
+    *C_p = d.Cp;
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_launch_counts(int64_t out[3], int32_t reset) {
+    if (!out) return MOE_ERR_NULL;
+    for (int i = 0; i < 3; ++i) {
+        out[i] = moe::g_launches[i].load();
+        if (reset) moe::g_launches[i].store(0);
+    }
+    return MOE_OK;
+}
+
+extern "C" const char* moe_status_string(moe_status s) {
+    switch (s) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_NULL: return "required pointer is NULL";
+        case MOE_ERR_SHAPE: return "invalid shape or partition";
+        case MOE_ERR_UNSUPPORTED: return "unsupported configuration";
+        case MOE_ERR_WORKSPACE: return "workspace too small";
+        case MOE_ERR_HIP: return "HIP call failed";
+    }
+    return "unknown status";
+}

@@ -1,0 +1,281 @@
+// bf16 grouped GEMM on the CDNA4 matrix cores for the expert FFN: the two linear
+// layers of every local expert (Section II-B2) and their four backward GEMMs
+// (Table II counts 2 forward and 4 backward GEMM units per partition, 5 with
+// recomputation).  Float accumulation in v_mfma_f32_32x32x16_bf16.
+//
+// One workgroup (4 wavefronts, 2x2) computes a BM x BN tile of one expert; each
+// wavefront owns (BM/2) x (BN/2) as 32x32 MFMA tiles.  Both operands are staged
+// in LDS with K contiguous (64 K-elements = one 128-byte row per tile row) and a
+// 16-byte-chunk XOR swizzle, so fragment reads are conflict-free ds_read_b128.
+// Operands whose K index is the slow one in memory (B of NN, both of TN) are
+// transposed in registers (8x8 blocks, v_perm_b32) on their way into LDS, which
+// keeps one MFMA loop for all three layouts.  LDS is double buffered and the
+// global loads for tile k+2 are in flight while tile k is multiplied.
+// Workgroup ids are remapped so that the workgroups resident on one XCD share
+// A/B panels through that XCD's L2.
+#include "common.h"
+#include "epilogue.h"
+
+namespace moe {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int G_BK = 64;
+constexpr int G_THREADS = 256;
+constexpr int G_ROWB = G_BK * 2;          // bytes of one LDS tile row
+
+__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+
+// ---- global -> registers --------------------------------------------------------
+// Direct: operand rows are K-contiguous.  R rows x 64 K = R*8 chunks of 16 bytes.
+template <int R>
+struct DirectTile {
+    static constexpr int N = R * 8 / G_THREADS;
+    uint4 v[N];
+    __device__ __forceinline__ void load(const bf16_t* P, int ld, int row0, int row_limit, int k0, int K, int tid) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int q = tid + i * G_THREADS;
+            const int row = q >> 3, c = q & 7;
+            const int gr = row0 + row, gk = k0 + c * 8;
+            if (gr < row_limit && gk < K)
+                v[i] = *reinterpret_cast<const uint4*>(P + (size_t)gr * ld + gk);
+            else
+                v[i] = make_uint4(0, 0, 0, 0);
+        }
+    }
+    __device__ __forceinline__ void store(char* lds, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int q = tid + i * G_THREADS;
+            const int row = q >> 3, c = q & 7;
+            *reinterpret_cast<uint4*>(lds + row * G_ROWB + ((c ^ swz(row)) << 4)) = v[i];
+        }
+    }
+};
+
+// Transposed: operand is [k][n] with n contiguous.  A thread takes an 8(k) x 8(n)
+// block, transposes it in registers and writes eight K-contiguous chunks.
+template <int R>
+struct TransTile {
+    static constexpr int NG = R / 8;                  // n-groups per tile
+    uint4 v[8];
+    __device__ __forceinline__ void load(const bf16_t* P, int ld, int n0, int n_limit, int k0, int K, int tid) {
+        const int ng = tid % NG, kg = tid / NG;
+        const int gn = n0 + ng * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int gk = k0 + kg * 8 + j;
+            if (tid < R && gn < n_limit && gk < K)
+                v[j] = *reinterpret_cast<const uint4*>(P + (size_t)gk * ld + gn);
+            else
+                v[j] = make_uint4(0, 0, 0, 0);
+        }
+    }
+    __device__ __forceinline__ void store(char* lds, int tid) const {
+        if (tid >= R) return;
+        const int ng = tid % NG, kg = tid / NG;
+        const unsigned* w = reinterpret_cast<const unsigned*>(v);   // w[j*4 + q]
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int q = i >> 1;
+            const unsigned sel = (i & 1) ? 0x07060302u : 0x05040100u;
+            uint4 o;
+            o.x = __builtin_amdgcn_perm(w[1 * 4 + q], w[0 * 4 + q], sel);
+            o.y = __builtin_amdgcn_perm(w[3 * 4 + q], w[2 * 4 + q], sel);
+            o.z = __builtin_amdgcn_perm(w[5 * 4 + q], w[4 * 4 + q], sel);
+            o.w = __builtin_amdgcn_perm(w[7 * 4 + q], w[6 * 4 + q], sel);
+            const int row = ng * 8 + i;
+            *reinterpret_cast<uint4*>(lds + row * G_ROWB + ((kg ^ swz(row)) << 4)) = o;
+        }
+    }
+};
+
+template <int LAY, int BM> struct ATile { typedef DirectTile<BM> type; };
+template <int BM> struct ATile<GEMM_TN, BM> { typedef TransTile<BM> type; };
+template <int LAY, int BN> struct BTile { typedef TransTile<BN> type; };
+template <int BN> struct BTile<GEMM_NT, BN> { typedef DirectTile<BN> type; };
+
+template <int LAY, int EPI, int BM, int BN>
+__global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TNN = WN / 32;
+    constexpr int STAGE = (BM + BN) * G_ROWB;
+
+    // ---- workgroup -> (expert, tile) with XCD-aware order ------------------------
+    // Hardware deals consecutive workgroup ids round-robin to the 8 XCDs; give each
+    // XCD a contiguous run of tiles, and walk tiles in groups of 4 tile-rows so the
+    // workgroups running together on an XCD reuse A and B panels in its L2.
+    int lin;
+    {
+        const int b = blockIdx.x;
+        const int per = nblocks >> 3;                   // nblocks is a multiple of 8
+        lin = (b & 7) * per + (b >> 3);
+    }
+    const int per_e = tiles_m * tiles_n;
+    const int e = lin / per_e;
+    if (e >= g.E) return;
+    int tm, tn;
+    {
+        const int rem = lin - e * per_e;
+        constexpr int GM = 4;
+        const int grp = rem / (GM * tiles_n);
+        const int first = grp * GM;
+        const int gsz = min(GM, tiles_m - first);
+        const int in = rem - grp * GM * tiles_n;
+        tm = first + in % gsz;
+        tn = in / gsz;
+    }
+    const int rows = g.counts[e];
+    int Mdim, Kdim;
+    if (LAY == GEMM_TN) { Mdim = g.Mo; Kdim = rows; } else { Mdim = rows; Kdim = g.K; }
+    const int m0 = tm * BM, n0 = tn * BN;
+    if (m0 >= Mdim || Kdim <= 0) return;
+
+    const bf16_t* A = (const bf16_t*)g.A + (size_t)e * g.a_estride;
+    const bf16_t* B = (const bf16_t*)g.B + (size_t)e * g.b_estride;
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int wm = wid >> 1, wn = wid & 1;
+
+    typename ATile<LAY, BM>::type ta;
+    typename BTile<LAY, BN>::type tb;
+    const int KT = (Kdim + G_BK - 1) / G_BK;
+
+    auto load_tiles = [&](int kt) {
+        ta.load(A, g.lda, m0, Mdim, kt * G_BK, Kdim, tid);
+        tb.load(B, g.ldb, n0, g.N, kt * G_BK, Kdim, tid);
+    };
+    auto store_tiles = [&](int stage) {
+        ta.store(smem + stage * STAGE, tid);
+        tb.store(smem + stage * STAGE + BM * G_ROWB, tid);
+    };
+
+    floatx16 acc[TM][TNN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TNN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // fragment addressing: lane reads tile row (lane & 31), logical chunk 2*kk + (lane >> 5)
+    int a_off[TM], a_sw[TM], b_off[TNN], b_sw[TNN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = wm * WM + i * 32 + (lane & 31);
+        a_off[i] = row * G_ROWB;
+        a_sw[i] = swz(row);
+    }
+#pragma unroll
+    for (int j = 0; j < TNN; ++j) {
+        const int row = wn * WN + j * 32 + (lane & 31);
+        b_off[j] = BM * G_ROWB + row * G_ROWB;
+        b_sw[j] = swz(row);
+    }
+    const int khalf = lane >> 5;
+
+    load_tiles(0);
+    store_tiles(0);
+    if (KT > 1) load_tiles(1);
+    __syncthreads();
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < KT) store_tiles(cur ^ 1);
+        if (kt + 2 < KT) load_tiles(kt + 2);
+        const char* base = smem + cur * STAGE;
+#pragma unroll
+        for (int kk = 0; kk < G_BK / 16; ++kk) {
+            bf16x8 af[TM], bfr[TNN];
+            const int c = kk * 2 + khalf;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[i] = *reinterpret_cast<const bf16x8*>(base + a_off[i] + ((c ^ a_sw[i]) << 4));
+#pragma unroll
+            for (int j = 0; j < TNN; ++j)
+                bfr[j] = *reinterpret_cast<const bf16x8*>(base + b_off[j] + ((c ^ b_sw[j]) << 4));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TNN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane holds row m = (lane & 31), columns 8*g4 + 4*(lane>>5) + 0..3 ----
+    // The lane id is passed through an empty asm so that none of the epilogue's
+    // address arithmetic is hoisted above the main loop, where registers are scarce.
+    int elane = lane;
+    asm volatile("" : "+v"(elane));
+    const int erow = elane & 31, ehalf = elane >> 5;
+    EpiCtx<bf16_t> c;
+    c.ldc = g.ldc; c.ldz = g.ldz;
+    c.C = (bf16_t*)g.C + (size_t)e * g.c_estride;
+    c.Cf = (float*)g.C + (size_t)e * g.c_estride;
+    c.Z = g.Z ? (bf16_t*)g.Z + (size_t)e * g.Cp * g.ldz : nullptr;
+    c.w = g.slot_w ? g.slot_w + (size_t)e * g.Cp : nullptr;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm * WM + i * 32 + erow;
+        float dot = 0.0f;
+#pragma unroll
+        for (int j = 0; j < TNN; ++j) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int n = n0 + wn * WN + j * 32 + g4 * 8 + ehalf * 4;
+                float v[4] = {acc[i][j][g4 * 4 + 0], acc[i][j][g4 * 4 + 1], acc[i][j][g4 * 4 + 2], acc[i][j][g4 * 4 + 3]};
+                if (m < Mdim && n < g.N) dot += epilogue4<bf16_t, EPI>(c, m, n, v);
+            }
+            __builtin_amdgcn_sched_barrier(0);   // keep one 32x32 tile's loads and stores together
+        }
+        if (EPI == EPI_DGELU && g.dw_part) {
+            dot += __shfl_xor(dot, 32, 64);
+            if (elane < 32 && m < Mdim) g.dw_part[((size_t)e * g.Cp + m) * g.dw_parts + tn * 2 + wn] = dot;
+        }
+    }
+}
+
+constexpr int DEF_BM = 256, DEF_BN = 256;
+int gemm_bf16_dw_parts(int H) { return ((H + DEF_BN - 1) / DEF_BN) * 2; }
+
+template <int LAY, int EPI, int BM, int BN>
+static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
+    const int Mmax = (LAY == GEMM_TN) ? a.Mo : a.Cp;
+    const int tiles_m = (Mmax + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+    int nblocks = a.E * tiles_m * tiles_n;
+    nblocks = (nblocks + 7) / 8 * 8;
+    constexpr int lds = 2 * (BM + BN) * G_ROWB;
+    auto kern = gemm_bf16_kernel<LAY, EPI, BM, BN>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return MOE_ERR_HIP;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(nblocks), dim3(G_THREADS), lds, s, a, tiles_m, tiles_n, nblocks);
+    count_launch(LC_GEMM);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+template <int LAY>
+static moe_status launch_lay(GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
+    switch (epi) {
+        case EPI_STORE: return launch_one<LAY, EPI_STORE, DEF_BM, DEF_BN>(a, s);
+        case EPI_GELU: return launch_one<LAY, EPI_GELU, DEF_BM, DEF_BN>(a, s);
+        case EPI_DGELU: return launch_one<LAY, EPI_DGELU, DEF_BM, DEF_BN>(a, s);
+        case EPI_ACCUM_F32: return launch_one<LAY, EPI_ACCUM_F32, DEF_BM, DEF_BN>(a, s);
+    }
+    return MOE_ERR_UNSUPPORTED;
+}
+
+moe_status gemm_bf16(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
+    if (a.dw_part && a.dw_parts != gemm_bf16_dw_parts(a.N)) return MOE_ERR_SHAPE;
+    if (lay == GEMM_NN) return launch_lay<GEMM_NN>(epi, a, s);
+    if (lay == GEMM_NT) return launch_lay<GEMM_NT>(epi, a, s);
+    return launch_lay<GEMM_TN>(epi, a, s);
+}
+
+}  // namespace moe

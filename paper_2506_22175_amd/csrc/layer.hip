@@ -1,0 +1,264 @@
+// The whole layer step as n micro-batch partitions on two HIP streams, with the
+// paper's memory reuse.
+//
+// Section III-B: the token batch is split along its batch dimension into n
+// partitions; for each one S (dispatch), C (expert computation) and R (combine)
+// run in that order, partitions are independent, S and R alternate on their
+// stream, and backward mirrors forward.  Section III-D: T_DI and T_DO of all
+// partitions share two buffers each and T_M shares one; what is overwritten is
+// restored in backward by sending T_I again (here: dispatching x again) and by
+// recomputing T_M from T_DI (Table II, strategy S4: 5 GEMMs and 3 exchanges in
+// backward instead of 4 and 2).
+//
+// Stream 0 carries the gate, S, R and their backward counterparts; stream 1
+// carries the GEMMs.  Cross-stream order is kept with events; a buffer shared by
+// partitions p and p+2 is rewritten only after its reader of partition p is done.
+#include "common.h"
+#include <vector>
+
+namespace moe {
+
+static inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Workspace {
+    // M-wide partition buffers
+    size_t DI, DO, dDO, dDI;          // offsets; each region holds nDI / nDO / 2 / 2 buffers
+    int nDI, nDO;
+    bool dDO_aliases_DO;
+    // H-wide
+    size_t Z, HT;                     // Z: nZ buffers; HT: one temporary (forward A, backward dZ)
+    int nZ;
+    // routing-class data
+    size_t slot_w, dw, dw_part, dL, gate_scratch, slot_scratch;
+    size_t bufM, bufH, dw_part_bytes;
+    size_t total, saved, temp, routing;
+};
+
+static moe_status plan(const moe_config* cfg, const Dims& d, Workspace* w) {
+    w->bufM = align_up((size_t)d.Rp * d.M * d.es);
+    w->bufH = align_up((size_t)d.Rp * d.H * d.es);
+    const bool reuse = d.reuse != MOE_REUSE_NONE;
+    w->nDI = (reuse && d.n > 2) ? 2 : d.n;
+    w->nDO = (reuse && d.n > 2) ? 2 : d.n;
+    w->nZ = d.reuse == MOE_REUSE_RECOMPUTE ? 1 : d.n;
+    w->dDO_aliases_DO = reuse;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    w->DI = take(w->bufM * w->nDI);
+    w->DO = take(w->bufM * w->nDO);
+    w->Z = take(w->bufH * w->nZ);
+    w->saved = off;
+    w->HT = take(w->bufH);
+    w->dDO = reuse ? w->DO : take(w->bufM * 2);
+    w->dDI = take(w->bufM * 2);
+    w->temp = off - w->saved;
+    const size_t r0 = off;
+    int parts = 0;
+    MOE_TRY(moe_dw_parts(cfg, &parts));
+    size_t gs = 0, ss = 0;
+    MOE_TRY(moe_gate_scratch_bytes(cfg, &gs));
+    MOE_TRY(moe_slot_scratch_bytes(cfg, &ss));
+    w->slot_w = take((size_t)d.n * d.Rp * sizeof(float));
+    w->dw = take((size_t)d.T * d.k * sizeof(float));
+    w->dw_part_bytes = align_up((size_t)d.Rp * parts * sizeof(float));
+    w->dw_part = take(w->dw_part_bytes * 2);
+    w->dL = take((size_t)d.T * d.E * sizeof(float));
+    w->gate_scratch = take(gs);
+    w->slot_scratch = take(ss);
+    w->routing = off - r0;
+    w->total = off;
+    return MOE_OK;
+}
+
+// Events are host objects; they are created once and reused by every call.
+static std::vector<hipEvent_t> g_events;
+static moe_status get_events(size_t n) {
+    while (g_events.size() < n) {
+        hipEvent_t e;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return MOE_ERR_HIP;
+        g_events.push_back(e);
+    }
+    return MOE_OK;
+}
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return MOE_ERR_HIP; } while (0)
+
+static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace& w, char* ws,
+                          const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* W2,
+                          void* y, float* logits, int* topk_idx, float* topk_w, int* slot, int* counts,
+                          hipStream_t s0, hipStream_t s1) {
+    const int n = d.n;
+    MOE_TRY(get_events(3 * (size_t)n + 1));
+    hipEvent_t* evS = g_events.data();
+    hipEvent_t* evC = evS + n;
+    hipEvent_t* evR = evC + n;
+    hipEvent_t evFork = g_events[3 * (size_t)n];
+
+    MOE_TRY(moe_route(cfg, x, Wg, gate_bias, logits, topk_idx, topk_w, s0));
+    MOE_TRY(moe_assign_slots(cfg, topk_idx, topk_w, slot, counts, (float*)(ws + w.slot_w),
+                             ws + w.slot_scratch, s0));
+    HIP_TRY(hipEventRecord(evFork, s0));
+    HIP_TRY(hipStreamWaitEvent(s1, evFork, 0));
+
+    auto DIbuf = [&](int p) { return ws + w.DI + w.bufM * (p % w.nDI); };
+    auto DObuf = [&](int p) { return ws + w.DO + w.bufM * (p % w.nDO); };
+    auto Zbuf = [&](int p) { return ws + w.Z + w.bufH * (p % w.nZ); };
+    const bool keepZ = d.reuse != MOE_REUSE_RECOMPUTE;
+
+    for (int p = 0; p <= n; ++p) {
+        if (p < n) {
+            // S_p.  A shared T_DI buffer was last read by C_{p-2}; R_{p-2}, already
+            // queued on this stream, waited for C_{p-2}.
+            MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
+            HIP_TRY(hipEventRecord(evS[p], s0));
+            // C_p
+            HIP_TRY(hipStreamWaitEvent(s1, evS[p], 0));
+            if (p >= w.nDO) HIP_TRY(hipStreamWaitEvent(s1, evR[p - w.nDO], 0));   // T_DO buffer free again
+            // with recomputation T_M is not kept: the activated rows go to the one
+            // shared H-wide buffer and the pre-activation is not written at all
+            void* Aout = keepZ ? (void*)(ws + w.HT) : (void*)Zbuf(p);
+            MOE_TRY(ffn_fwd(d, p, DIbuf(p), counts, W1, W2, keepZ ? Zbuf(p) : nullptr, Aout, DObuf(p), s1));
+            HIP_TRY(hipEventRecord(evC[p], s1));
+        }
+        if (p >= 1) {
+            // R_{p-1}, issued after S_p so that S and R alternate on stream 0
+            HIP_TRY(hipStreamWaitEvent(s0, evC[p - 1], 0));
+            MOE_TRY(moe_combine(cfg, p - 1, DObuf(p - 1), slot, topk_w, y, s0));
+            HIP_TRY(hipEventRecord(evR[p - 1], s0));
+        }
+    }
+    return MOE_OK;
+}
+
+static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace& w, char* ws,
+                           const void* x, const void* dy, const void* Wg, const void* W1, const void* W2,
+                           void* dx, float* dWg, float* dW1, float* dW2,
+                           const float* logits, const int* topk_idx, const int* slot, const int* counts,
+                           hipStream_t s0, hipStream_t s1) {
+    const int n = d.n;
+    MOE_TRY(get_events(3 * (size_t)n + 1));
+    hipEvent_t* evS = g_events.data();        // R'_p done (rows of dy, and of x again, are in place)
+    hipEvent_t* evC = evS + n;                // backward GEMMs of p done
+    hipEvent_t* evD = evC + n;                // S'_p done (dDI and dw_part of p consumed)
+    hipEvent_t evFork = g_events[3 * (size_t)n];
+    const bool reuse = d.reuse != MOE_REUSE_NONE;
+    const bool recompute = d.reuse == MOE_REUSE_RECOMPUTE;
+
+    auto DIbuf = [&](int p) { return ws + w.DI + w.bufM * (p % w.nDI); };
+    auto DObuf = [&](int p) { return ws + w.DO + w.bufM * (p % w.nDO); };
+    auto Zbuf = [&](int p) { return ws + w.Z + w.bufH * (p % w.nZ); };
+    auto dDObuf = [&](int p) { return ws + w.dDO + w.bufM * (p % 2); };
+    auto dDIbuf = [&](int p) { return ws + w.dDI + w.bufM * (p % 2); };
+    auto dwpart = [&](int p) { return (float*)(ws + w.dw_part + w.dw_part_bytes * (p % 2)); };
+    float* dw = (float*)(ws + w.dw);
+    float* dL = (float*)(ws + w.dL);
+    const float* slot_w = (const float*)(ws + w.slot_w);
+
+    HIP_TRY(hipEventRecord(evFork, s0));
+    HIP_TRY(hipStreamWaitEvent(s1, evFork, 0));
+
+    for (int p = 0; p <= n; ++p) {
+        if (p < n) {
+            // R'_p: rows of dy to the experts.  Their buffer (and the re-dispatched T_DI
+            // buffer) was last read by the GEMMs of partition p-2.
+            if (p >= 2) HIP_TRY(hipStreamWaitEvent(s0, evC[p - 2], 0));
+            if (reuse) {
+                MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), nullptr, nullptr, s0));
+                MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));   // T_DI from T_I again
+            } else {
+                // T_DO was kept: the combine-weight gradient is <dy_t, T_DO row>
+                MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), DObuf(p), dw, s0));
+            }
+            HIP_TRY(hipEventRecord(evS[p], s0));
+            // C'_p
+            HIP_TRY(hipStreamWaitEvent(s1, evS[p], 0));
+            if (p >= 2) HIP_TRY(hipStreamWaitEvent(s1, evD[p - 2], 0));
+            MOE_TRY(ffn_bwd(d, p, recompute ? 1 : 0, DIbuf(p), Zbuf(p), dDObuf(p), counts, slot_w, W1, W2,
+                            ws + w.HT, dDIbuf(p), dW1, dW2, reuse ? dwpart(p) : nullptr, s1));
+            HIP_TRY(hipEventRecord(evC[p], s1));
+        }
+        if (p >= 1) {
+            // S'_{p-1}: gate backward and rows of dDI back to token order
+            const int q = p - 1;
+            HIP_TRY(hipStreamWaitEvent(s0, evC[q], 0));
+            MOE_TRY(moe_gate_bwd(cfg, q, x, logits, topk_idx, slot, reuse ? nullptr : dw,
+                                 reuse ? dwpart(q) : nullptr, dL, dWg, ws + w.gate_scratch, s0));
+            MOE_TRY(moe_dispatch_bwd(cfg, q, dDIbuf(q), slot, dL, Wg, dx, s0));
+            HIP_TRY(hipEventRecord(evD[q], s0));
+        }
+    }
+    return MOE_OK;
+}
+
+static moe_status setup(const moe_config* cfg, Dims* d, Workspace* w, void* workspace, size_t workspace_bytes,
+                        void* const* streams, int n_streams, hipStream_t* s0, hipStream_t* s1) {
+    MOE_TRY(make_dims(cfg, d));
+    if (!workspace || !streams) return MOE_ERR_NULL;
+    if (n_streams < 2) return MOE_ERR_SHAPE;
+    MOE_TRY(plan(cfg, *d, w));
+    if (workspace_bytes < w->total) return MOE_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_WORKSPACE;
+    *s0 = (hipStream_t)streams[0];
+    *s1 = (hipStream_t)streams[1];
+    return MOE_OK;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" moe_status moe_workspace_bytes(const moe_config* cfg, size_t* total, size_t* saved,
+                                          size_t* temp, size_t* routing) {
+    Dims d;
+    MOE_TRY(make_dims(cfg, &d));
+    Workspace w;
+    MOE_TRY(plan(cfg, d, &w));
+    if (total) *total = w.total;
+    if (saved) *saved = w.saved;
+    if (temp) *temp = w.temp;
+    if (routing) *routing = w.routing;
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_layer_forward(const moe_config* cfg, const void* x,
+                                        const void* Wg, const float* gate_bias, const void* W1, const void* W2,
+                                        void* y, float* logits, int32_t* topk_idx, float* topk_w,
+                                        int32_t* slot, int32_t* counts,
+                                        void* workspace, size_t workspace_bytes,
+                                        void* const* streams, int32_t n_streams) {
+    Dims d; Workspace w; hipStream_t s0, s1;
+    MOE_TRY(setup(cfg, &d, &w, workspace, workspace_bytes, streams, n_streams, &s0, &s1));
+    if (!x || !Wg || !W1 || !W2 || !y || !logits || !topk_idx || !topk_w || !slot || !counts) return MOE_ERR_NULL;
+    return forward(cfg, d, w, (char*)workspace, x, Wg, gate_bias, W1, W2, y, logits, topk_idx, topk_w, slot,
+                   counts, s0, s1);
+}
+
+extern "C" moe_status moe_layer_backward(const moe_config* cfg, const void* x, const void* dy,
+                                         const void* Wg, const void* W1, const void* W2,
+                                         void* dx, float* dWg, float* dW1, float* dW2,
+                                         const float* logits, const int32_t* topk_idx, const float* topk_w,
+                                         const int32_t* slot, const int32_t* counts,
+                                         void* workspace, size_t workspace_bytes,
+                                         void* const* streams, int32_t n_streams) {
+    Dims d; Workspace w; hipStream_t s0, s1;
+    MOE_TRY(setup(cfg, &d, &w, workspace, workspace_bytes, streams, n_streams, &s0, &s1));
+    if (!x || !dy || !Wg || !W1 || !W2 || !dx || !dWg || !dW1 || !dW2 || !logits || !topk_idx || !topk_w ||
+        !slot || !counts) return MOE_ERR_NULL;
+    return backward(cfg, d, w, (char*)workspace, x, dy, Wg, W1, W2, dx, dWg, dW1, dW2, logits, topk_idx, slot,
+                    counts, s0, s1);
+}
+
+extern "C" moe_status moe_layer_step(const moe_config* cfg, const void* x, const void* dy,
+                                     const void* Wg, const float* gate_bias, const void* W1, const void* W2,
+                                     void* y, void* dx, float* dWg, float* dW1, float* dW2,
+                                     float* logits, int32_t* topk_idx, float* topk_w, int32_t* slot, int32_t* counts,
+                                     void* workspace, size_t workspace_bytes,
+                                     void* const* streams, int32_t n_streams) {
+    Dims d; Workspace w; hipStream_t s0, s1;
+    MOE_TRY(setup(cfg, &d, &w, workspace, workspace_bytes, streams, n_streams, &s0, &s1));
+    if (!x || !dy || !Wg || !W1 || !W2 || !y || !dx || !dWg || !dW1 || !dW2 || !logits || !topk_idx ||
+        !topk_w || !slot || !counts) return MOE_ERR_NULL;
+    MOE_TRY(forward(cfg, d, w, (char*)workspace, x, Wg, gate_bias, W1, W2, y, logits, topk_idx, topk_w, slot,
+                    counts, s0, s1));
+    return backward(cfg, d, w, (char*)workspace, x, dy, Wg, W1, W2, dx, dWg, dW1, dW2, logits, topk_idx, slot,
+                    counts, s0, s1);
+}

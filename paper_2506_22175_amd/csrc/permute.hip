@@ -1,0 +1,355 @@
+// Dispatch (S), combine (R) and their backward counterparts for one partition.
+// In the paper S and R are the two All-to-All exchanges of expert parallelism
+// (Fig. 1, Section II-A); on one GPU they are local row permutations between the
+// token-ordered tensors T_I / T_O and the expert-contiguous T_DI / T_DO.  They
+// are bound by HBM: every kernel moves whole rows with 16-byte accesses, one
+// wavefront per token, and reads each token row once however many experts it
+// goes to.
+#include "common.h"
+
+namespace moe {
+
+constexpr int PERM_THREADS = 256;
+constexpr int PERM_WAVES = PERM_THREADS / 64;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// DI[slot[t,j]] = src[t]; optionally dw[t,j] = <src[t], saved[slot[t,j]]>.
+// U = 16-byte units per row.
+template <typename T, bool WITH_DW>
+__global__ __launch_bounds__(PERM_THREADS) void dispatch_kernel(
+    const T* __restrict__ src, const int* __restrict__ slot, T* __restrict__ dst,
+    const T* __restrict__ saved, float* __restrict__ dw, int t_begin, int t_count, int M, int k) {
+    const int lane = threadIdx.x & 63;
+    const int tl = blockIdx.x * PERM_WAVES + (threadIdx.x >> 6);
+    if (tl >= t_count) return;
+    const int t = t_begin + tl;
+    constexpr int EPU = 16 / sizeof(T);            // elements per 16-byte unit
+    const int U = M / EPU;
+    int s[8];
+    for (int j = 0; j < k; ++j) s[j] = slot[(size_t)t * k + j];
+    const uint4* in = reinterpret_cast<const uint4*>(src + (size_t)t * M);
+    float dot[8];
+    if (WITH_DW) for (int j = 0; j < k; ++j) dot[j] = 0.0f;
+    for (int c0 = 0; c0 < U; c0 += 256) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int c = c0 + u * 64 + lane;
+            if (c < U) v[u] = in[c];
+        }
+        for (int j = 0; j < k; ++j) {
+            if (s[j] < 0) continue;
+            uint4* out = reinterpret_cast<uint4*>(dst + (size_t)s[j] * M);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int c = c0 + u * 64 + lane;
+                if (c < U) {
+                    out[c] = v[u];
+                    if (WITH_DW) {
+                        uint4 o = reinterpret_cast<const uint4*>(saved + (size_t)s[j] * M)[c];
+                        const T* a = reinterpret_cast<const T*>(&v[u]);
+                        const T* b = reinterpret_cast<const T*>(&o);
+#pragma unroll
+                        for (int i = 0; i < EPU; ++i) dot[j] = fmaf(Elem<T>::ld(a + i), Elem<T>::ld(b + i), dot[j]);
+                    }
+                }
+            }
+        }
+    }
+    if (WITH_DW) {
+        for (int j = 0; j < k; ++j) {
+            float d = wave_sum(dot[j]);
+            if (lane == 0) dw[(size_t)t * k + j] = s[j] >= 0 ? d : 0.0f;
+        }
+    }
+}
+
+// y[t] = sum_j w[t,j] * DO[slot[t,j]]  (float accumulation, ascending j)
+template <typename T>
+__global__ __launch_bounds__(PERM_THREADS) void combine_kernel(
+    const T* __restrict__ DO, const int* __restrict__ slot, const float* __restrict__ w,
+    T* __restrict__ y, int t_begin, int t_count, int M, int k) {
+    const int lane = threadIdx.x & 63;
+    const int tl = blockIdx.x * PERM_WAVES + (threadIdx.x >> 6);
+    if (tl >= t_count) return;
+    const int t = t_begin + tl;
+    int s[8];
+    float ws[8];
+    for (int j = 0; j < k; ++j) { s[j] = slot[(size_t)t * k + j]; ws[j] = w[(size_t)t * k + j]; }
+    for (int c = lane * 8; c < M; c += 512) {
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+        for (int j = 0; j < k; ++j) {
+            if (s[j] < 0) continue;
+            float r[8];
+            Vec8<T>::load(DO + (size_t)s[j] * M + c, r);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = fmaf(ws[j], r[i], acc[i]);
+        }
+        Vec8<T>::store(y + (size_t)t * M + c, acc);
+    }
+}
+
+// dx[t] = sum_j dDI[slot[t,j]] + dL[t,:] Wg^T.  A thread owns eight columns and
+// keeps their gate weights in registers across TOKB tokens.
+constexpr int DXB_TOK = 32;
+template <typename T, int EC>
+__global__ __launch_bounds__(PERM_THREADS) void dispatch_bwd_kernel(
+    const T* __restrict__ dDI, const int* __restrict__ slot, const float* __restrict__ dL,
+    const T* __restrict__ Wg, T* __restrict__ dx, int t_begin, int t_count, int M, int E, int k) {
+    const int c = (blockIdx.x * PERM_THREADS + threadIdx.x) * 8;
+    if (c >= M) return;
+    float wg[8][EC];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < EC; ++e) wg[i][e] = e < E ? Elem<T>::ld(Wg + (size_t)(c + i) * E + e) : 0.0f;
+    const int tl0 = blockIdx.y * DXB_TOK;
+    const int tl1 = min(tl0 + DXB_TOK, t_count);
+    for (int tl = tl0; tl < tl1; ++tl) {
+        const int t = t_begin + tl;
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+        for (int j = 0; j < k; ++j) {
+            int s = slot[(size_t)t * k + j];
+            if (s < 0) continue;
+            float r[8];
+            Vec8<T>::load(dDI + (size_t)s * M + c, r);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] += r[i];
+        }
+        for (int e0 = 0; e0 < E; e0 += EC) {
+#pragma unroll
+            for (int e = 0; e < EC; ++e) {
+                if (e0 + e < E) {
+                    float g = dL[(size_t)t * E + e0 + e];
+                    if (E <= EC) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) acc[i] = fmaf(g, wg[i][e], acc[i]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            acc[i] = fmaf(g, Elem<T>::ld(Wg + (size_t)(c + i) * E + e0 + e), acc[i]);
+                    }
+                }
+            }
+        }
+        Vec8<T>::store(dx + (size_t)t * M + c, acc);
+    }
+}
+
+// ---- gate backward ------------------------------------------------------------
+
+// dL[t,e] = p[t,e] * (dp[t,e] - sum_e' dp[t,e'] p[t,e']) with dp nonzero only at the
+// chosen experts.  One thread per token.
+__global__ __launch_bounds__(256) void gate_dl_kernel(
+    const float* __restrict__ logits, const int* __restrict__ topk_idx, const int* __restrict__ slot,
+    const float* __restrict__ dw, const float* __restrict__ dw_part, int parts,
+    float* __restrict__ dL, int t_begin, int t_count, int E, int k) {
+    const int tl = blockIdx.x * 256 + threadIdx.x;
+    if (tl >= t_count) return;
+    const int t = t_begin + tl;
+    const float* lg = logits + (size_t)t * E;
+    float mx = -INFINITY;
+    for (int e = 0; e < E; ++e) mx = fmaxf(mx, lg[e]);
+    float sum = 0.0f;
+    for (int e = 0; e < E; ++e) sum += expf(lg[e] - mx);
+    const float inv = 1.0f / sum;
+    float g[8];
+    int ids[8];
+    float inner = 0.0f;
+    for (int j = 0; j < k; ++j) {
+        ids[j] = topk_idx[(size_t)t * k + j];
+        float v = 0.0f;
+        if (dw_part) {
+            int s = slot[(size_t)t * k + j];
+            if (s >= 0)
+                for (int c = 0; c < parts; ++c) v += dw_part[(size_t)s * parts + c];
+        } else {
+            v = dw[(size_t)t * k + j];
+        }
+        g[j] = v;
+        inner = fmaf(v, expf(lg[ids[j]] - mx) * inv, inner);
+    }
+    for (int e = 0; e < E; ++e) {
+        float p = expf(lg[e] - mx) * inv;
+        float dp = 0.0f;
+        for (int j = 0; j < k; ++j) if (ids[j] == e) dp = g[j];
+        dL[(size_t)t * E + e] = p * (dp - inner);
+    }
+}
+
+// part[b][d][e] = sum over the block's tokens of x[t,d] * dL[t,e]
+constexpr int DWG_TOK = 256;
+template <typename T>
+__global__ __launch_bounds__(PERM_THREADS) void gate_dwg_partial_kernel(
+    const T* __restrict__ x, const float* __restrict__ dL, float* __restrict__ part,
+    int t_begin, int t_count, int M, int E) {
+    __shared__ float sdl[DWG_TOK][16];
+    const int c = (blockIdx.x * PERM_THREADS + threadIdx.x) * 8;
+    const int tl0 = blockIdx.y * DWG_TOK;
+    const int nt = min(DWG_TOK, t_count - tl0);
+    const int e0 = blockIdx.z * 16;
+    const int ne = min(16, E - e0);
+    for (int q = threadIdx.x; q < nt * 16; q += PERM_THREADS) {
+        int i = q / 16, e = q % 16;
+        sdl[i][e] = e < ne ? dL[(size_t)(t_begin + tl0 + i) * E + e0 + e] : 0.0f;
+    }
+    __syncthreads();
+    if (c >= M) return;
+    float acc[8][16];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
+    for (int i = 0; i < nt; ++i) {
+        float xv[8];
+        Vec8<T>::load(x + (size_t)(t_begin + tl0 + i) * M + c, xv);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            float g = sdl[i][e];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q][e] = fmaf(xv[q], g, acc[q][e]);
+        }
+    }
+    float* out = part + ((size_t)blockIdx.y * M + c) * E + e0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            if (e < ne) out[(size_t)q * E + e] = acc[q][e];
+}
+
+__global__ __launch_bounds__(256) void gate_dwg_reduce_kernel(
+    const float* __restrict__ part, float* __restrict__ dWg, int nblk, int ME) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= ME) return;
+    float s = 0.0f;
+    for (int b = 0; b < nblk; ++b) s += part[(size_t)b * ME + i];
+    dWg[i] += s;
+}
+
+template <typename T>
+static moe_status dispatch_t(const Dims& d, int part, const void* src, const int* slot, void* DI,
+                             const void* saved, float* dw, hipStream_t s) {
+    dim3 grid((d.Tp + PERM_WAVES - 1) / PERM_WAVES);
+    if (saved && dw)
+        hipLaunchKernelGGL((dispatch_kernel<T, true>), grid, dim3(PERM_THREADS), 0, s, (const T*)src, slot,
+                           (T*)DI, (const T*)saved, dw, part * d.Tp, d.Tp, d.M, d.k);
+    else
+        hipLaunchKernelGGL((dispatch_kernel<T, false>), grid, dim3(PERM_THREADS), 0, s, (const T*)src, slot,
+                           (T*)DI, (const T*)nullptr, (float*)nullptr, part * d.Tp, d.Tp, d.M, d.k);
+    count_launch(LC_PERMUTE);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+template <typename T>
+static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const int* slot, const float* dL,
+                                 const void* Wg, void* dx, hipStream_t s) {
+    dim3 grid((d.M / 8 + PERM_THREADS - 1) / PERM_THREADS, (d.Tp + DXB_TOK - 1) / DXB_TOK);
+#define LAUNCH_DXB(EC) hipLaunchKernelGGL((dispatch_bwd_kernel<T, EC>), grid, dim3(PERM_THREADS), 0, s, \
+        (const T*)dDI, slot, dL, (const T*)Wg, (T*)dx, part * d.Tp, d.Tp, d.M, d.E, d.k)
+    if (d.E <= 4) LAUNCH_DXB(4);
+    else if (d.E <= 8) LAUNCH_DXB(8);
+    else LAUNCH_DXB(16);
+#undef LAUNCH_DXB
+    count_launch(LC_PERMUTE);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+template <typename T>
+static moe_status gate_bwd_t(const Dims& d, int part, const void* x, const float* logits, const int* idx,
+                             const int* slot, const float* dw, const float* dw_part, int parts,
+                             float* dL, float* dWg, void* scratch, hipStream_t s) {
+    hipLaunchKernelGGL(gate_dl_kernel, dim3((d.Tp + 255) / 256), dim3(256), 0, s, logits, idx, slot, dw,
+                       dw_part, parts, dL, part * d.Tp, d.Tp, d.E, d.k);
+    MOE_CHECK_LAUNCH();
+    const int nblk = (d.Tp + DWG_TOK - 1) / DWG_TOK;
+    dim3 grid((d.M / 8 + PERM_THREADS - 1) / PERM_THREADS, nblk, (d.E + 15) / 16);
+    hipLaunchKernelGGL((gate_dwg_partial_kernel<T>), grid, dim3(PERM_THREADS), 0, s, (const T*)x, dL,
+                       (float*)scratch, part * d.Tp, d.Tp, d.M, d.E);
+    MOE_CHECK_LAUNCH();
+    const int ME = d.M * d.E;
+    hipLaunchKernelGGL(gate_dwg_reduce_kernel, dim3((ME + 255) / 256), dim3(256), 0, s,
+                       (const float*)scratch, dWg, nblk, ME);
+    count_launch(LC_OTHER, 3);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" moe_status moe_dispatch(const moe_config* cfg, int32_t part, const void* src, const int32_t* slot,
+                                   void* DI, const void* dO_saved, float* dw, void* stream) {
+    Dims d;
+    MOE_TRY(make_dims(cfg, &d));
+    MOE_TRY(check_part(d, part));
+    if (!src || !slot || !DI) return MOE_ERR_NULL;
+    if (d.dtype == MOE_F32) return dispatch_t<float>(d, part, src, slot, DI, dO_saved, dw, (hipStream_t)stream);
+    return dispatch_t<bf16_t>(d, part, src, slot, DI, dO_saved, dw, (hipStream_t)stream);
+}
+
+extern "C" moe_status moe_combine(const moe_config* cfg, int32_t part, const void* DO, const int32_t* slot,
+                                  const float* topk_w, void* y, void* stream) {
+    Dims d;
+    MOE_TRY(make_dims(cfg, &d));
+    MOE_TRY(check_part(d, part));
+    if (!DO || !slot || !topk_w || !y) return MOE_ERR_NULL;
+    dim3 grid((d.Tp + PERM_WAVES - 1) / PERM_WAVES);
+    hipStream_t s = (hipStream_t)stream;
+    if (d.dtype == MOE_F32)
+        hipLaunchKernelGGL((combine_kernel<float>), grid, dim3(PERM_THREADS), 0, s, (const float*)DO, slot,
+                           topk_w, (float*)y, part * d.Tp, d.Tp, d.M, d.k);
+    else
+        hipLaunchKernelGGL((combine_kernel<bf16_t>), grid, dim3(PERM_THREADS), 0, s, (const bf16_t*)DO, slot,
+                           topk_w, (bf16_t*)y, part * d.Tp, d.Tp, d.M, d.k);
+    count_launch(LC_PERMUTE);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_dispatch_bwd(const moe_config* cfg, int32_t part, const void* dDI, const int32_t* slot,
+                                       const float* dL, const void* Wg, void* dx, void* stream) {
+    Dims d;
+    MOE_TRY(make_dims(cfg, &d));
+    MOE_TRY(check_part(d, part));
+    if (!dDI || !slot || !dL || !Wg || !dx) return MOE_ERR_NULL;
+    if (d.dtype == MOE_F32) return dispatch_bwd_t<float>(d, part, dDI, slot, dL, Wg, dx, (hipStream_t)stream);
+    return dispatch_bwd_t<bf16_t>(d, part, dDI, slot, dL, Wg, dx, (hipStream_t)stream);
+}
+
+extern "C" moe_status moe_gate_scratch_bytes(const moe_config* cfg, size_t* bytes) {
+    Dims d;
+    MOE_TRY(make_dims(cfg, &d));
+    if (!bytes) return MOE_ERR_NULL;
+    *bytes = (size_t)((d.Tp + DWG_TOK - 1) / DWG_TOK) * d.M * d.E * sizeof(float);
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_gate_bwd(const moe_config* cfg, int32_t part, const void* x, const float* logits,
+                                   const int32_t* topk_idx, const int32_t* slot, const float* dw,
+                                   const float* dw_part, float* dL, float* dWg, void* scratch, void* stream) {
+    Dims d;
+    MOE_TRY(make_dims(cfg, &d));
+    MOE_TRY(check_part(d, part));
+    if (!x || !logits || !topk_idx || !slot || !dL || !dWg || !scratch) return MOE_ERR_NULL;
+    if (!dw && !dw_part) return MOE_ERR_NULL;
+    int parts = 0;
+    MOE_TRY(moe_dw_parts(cfg, &parts));
+    if (d.dtype == MOE_F32)
+        return gate_bwd_t<float>(d, part, x, logits, topk_idx, slot, dw, dw_part, parts, dL, dWg, scratch,
+                                 (hipStream_t)stream);
+    return gate_bwd_t<bf16_t>(d, part, x, logits, topk_idx, slot, dw, dw_part, parts, dL, dWg, scratch,
+                              (hipStream_t)stream);
+}

@@ -1,0 +1,102 @@
+// Capacity-bounded slot assignment.  The paper has no capacity (its batch is
+// "dynamic", Section III-C); here every micro-batch of Section III-B is an
+// independent MoE call with C_p rows per expert, which is what makes partition
+// buffers exactly 1/n of the whole (Section III-D).  Inside a partition,
+// positions are granted choice-major then in token order, by a stable ranking:
+// per-block histograms, a prefix over the blocks that come earlier in that
+// order, and a stable in-block rank.  No result depends on atomic ordering.
+#include "common.h"
+
+namespace moe {
+
+constexpr int SLOT_BLOCK = 1024;   // assignments ranked by one workgroup
+
+// hist[((p*k + j)*nb + b)*E + e] = number of tokens of block b (partition p) whose
+// j-th choice is expert e
+__global__ __launch_bounds__(SLOT_BLOCK) void slot_hist_kernel(
+    const int* __restrict__ topk_idx, int* __restrict__ hist, int Tp, int k, int E, int nb) {
+    __shared__ int h[64];
+    const int b = blockIdx.x, j = blockIdx.y, p = blockIdx.z;
+    if (threadIdx.x < 64) h[threadIdx.x] = 0;
+    __syncthreads();
+    const int tl = b * SLOT_BLOCK + threadIdx.x;
+    if (tl < Tp) {
+        int e = topk_idx[(size_t)(p * Tp + tl) * k + j];
+        atomicAdd(&h[e], 1);             // integer counts: order does not matter
+    }
+    __syncthreads();
+    if (threadIdx.x < E) hist[((size_t)(p * k + j) * nb + b) * E + threadIdx.x] = h[threadIdx.x];
+}
+
+__global__ __launch_bounds__(SLOT_BLOCK) void slot_assign_kernel(
+    const int* __restrict__ topk_idx, const float* __restrict__ topk_w, const int* __restrict__ hist,
+    int* __restrict__ slot, int* __restrict__ counts, float* __restrict__ slot_w,
+    int Tp, int k, int E, int nb, int Cp) {
+    __shared__ int base[64];
+    __shared__ int wcount[SLOT_BLOCK / 64][64];
+    const int b = blockIdx.x, j = blockIdx.y, p = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    if (tid < 64) {
+        int before = 0, total = 0;
+        if (tid < E) {
+            const int mine = j * nb + b;
+            for (int q = 0; q < k * nb; ++q) {
+                int v = hist[((size_t)p * k * nb + q) * E + tid];
+                total += v;
+                if (q < mine) before += v;
+            }
+            if (b == 0 && j == 0) counts[p * E + tid] = total < Cp ? total : Cp;
+        }
+        base[tid] = before;
+    }
+    const int tl = b * SLOT_BLOCK + tid;
+    const bool valid = tl < Tp;
+    const int t = p * Tp + tl;
+    const int my_e = valid ? topk_idx[(size_t)t * k + j] : -1;
+    int rank = 0;
+    for (int e = 0; e < E; ++e) {
+        unsigned long long m = __ballot(my_e == e);
+        if (my_e == e) rank = __popcll(m & ((1ull << lane) - 1ull));
+        if (lane == 0) wcount[wid][e] = __popcll(m);
+    }
+    __syncthreads();
+    if (valid) {
+        int pos = base[my_e] + rank;
+        for (int w = 0; w < wid; ++w) pos += wcount[w][my_e];
+        int s = pos < Cp ? my_e * Cp + pos : -1;
+        slot[(size_t)t * k + j] = s;
+        if (s >= 0 && slot_w) slot_w[(size_t)p * E * Cp + s] = topk_w[(size_t)t * k + j];
+    }
+}
+
+}  // namespace moe
+
+extern "C" moe_status moe_slot_scratch_bytes(const moe_config* cfg, size_t* bytes) {
+    moe::Dims d;
+    MOE_TRY(moe::make_dims(cfg, &d));
+    if (!bytes) return MOE_ERR_NULL;
+    int nb = (d.Tp + moe::SLOT_BLOCK - 1) / moe::SLOT_BLOCK;
+    *bytes = (size_t)d.n * d.k * nb * d.E * sizeof(int);
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_assign_slots(const moe_config* cfg, const int32_t* topk_idx, const float* topk_w,
+                                       int32_t* slot, int32_t* counts, float* slot_w,
+                                       void* scratch, void* stream) {
+    moe::Dims d;
+    MOE_TRY(moe::make_dims(cfg, &d));
+    if (!topk_idx || !slot || !counts || !scratch) return MOE_ERR_NULL;
+    if (slot_w && !topk_w) return MOE_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    int nb = (d.Tp + moe::SLOT_BLOCK - 1) / moe::SLOT_BLOCK;
+    dim3 grid(nb, d.k, d.n);
+    hipLaunchKernelGGL(moe::slot_hist_kernel, grid, dim3(moe::SLOT_BLOCK), 0, s,
+                       topk_idx, (int*)scratch, d.Tp, d.k, d.E, nb);
+    MOE_CHECK_LAUNCH();
+    hipLaunchKernelGGL(moe::slot_assign_kernel, grid, dim3(moe::SLOT_BLOCK), 0, s,
+                       topk_idx, topk_w, (const int*)scratch, slot, counts, slot_w,
+                       d.Tp, d.k, d.E, nb, d.Cp);
+    moe::count_launch(moe::LC_OTHER, 2);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}

@@ -1,0 +1,111 @@
+"""Device-memory plumbing around the C ABI: upload inputs, allocate outputs and the
+workspace with torch, call moe_layer_step, download results.  No arithmetic of the
+layer happens here."""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+_TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
+_MOE_DT = {"f32": B.MOE_F32, "bf16": B.MOE_BF16}
+
+
+def to_device(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
+    """float32 host array -> device tensor of the storage type (values must be representable)."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device).to(_TORCH_DT[dtype]).contiguous()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        t = t.float()
+    return t.cpu().numpy()
+
+
+class LayerState:
+    """All device buffers of one layer step for a given configuration."""
+
+    def __init__(self, T, M, H, E, k, capacity_factor, n_partitions=1, dtype="bf16", reuse=0, device="cuda:0",
+                 second_stream: bool = True):
+        self.dtype = dtype
+        self.device = device
+        self.cfg = B.make_config(T, M, H, E, k, capacity_factor, n_partitions, _MOE_DT[dtype], reuse)
+        self.C_p = B.moe_capacity(self.cfg)
+        self.ws_total, self.ws_saved, self.ws_temp, self.ws_routing = B.moe_workspace_bytes(self.cfg)
+        td = _TORCH_DT[dtype]
+        dev = device
+        self.y = torch.empty((T, M), dtype=td, device=dev)
+        self.dx = torch.empty((T, M), dtype=td, device=dev)
+        self.dWg = torch.zeros((M, E), dtype=torch.float32, device=dev)
+        self.dW1 = torch.zeros((E, M, H), dtype=torch.float32, device=dev)
+        self.dW2 = torch.zeros((E, H, M), dtype=torch.float32, device=dev)
+        self.logits = torch.empty((T, E), dtype=torch.float32, device=dev)
+        self.topk_idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+        self.topk_w = torch.empty((T, k), dtype=torch.float32, device=dev)
+        self.slot = torch.empty((T, k), dtype=torch.int32, device=dev)
+        self.counts = torch.empty((n_partitions, E), dtype=torch.int32, device=dev)
+        self.workspace = torch.empty((self.ws_total,), dtype=torch.uint8, device=dev)
+        self.s0 = torch.cuda.current_stream(dev)
+        self.s1 = torch.cuda.Stream(dev) if second_stream else self.s0
+        self.inputs: Dict[str, Optional[torch.Tensor]] = {}
+
+    def upload(self, inp: Dict[str, np.ndarray]):
+        for name in ("x", "Wg", "W1", "W2", "dy"):
+            self.inputs[name] = to_device(inp[name], self.dtype, self.device)
+        gb = inp.get("gate_bias")
+        self.inputs["gate_bias"] = None if gb is None else torch.from_numpy(np.asarray(gb, dtype=np.float32)).to(self.device)
+
+    def zero_grads(self):
+        self.dWg.zero_()
+        self.dW1.zero_()
+        self.dW2.zero_()
+
+    def poison(self):
+        """Fill everything the step must overwrite with NaN / -2 so stale data shows."""
+        self.workspace.fill_(0xFF)          # 0xFFFF bf16 and 0xFFFFFFFF float are NaN
+        for t in (self.y, self.dx, self.logits, self.topk_w):
+            t.fill_(float("nan"))
+        self.topk_idx.fill_(-2)
+        self.slot.fill_(-2)
+        self.counts.fill_(-2)
+
+    def step(self):
+        i = self.inputs
+        B.moe_layer_step(self.cfg, i["x"], i["dy"], i["Wg"], i["gate_bias"], i["W1"], i["W2"], self.y, self.dx,
+                         self.dWg, self.dW1, self.dW2, self.logits, self.topk_idx, self.topk_w, self.slot,
+                         self.counts, self.workspace, [self.s0, self.s1])
+
+    def forward(self):
+        i = self.inputs
+        B.moe_layer_forward(self.cfg, i["x"], i["Wg"], i["gate_bias"], i["W1"], i["W2"], self.y, self.logits,
+                            self.topk_idx, self.topk_w, self.slot, self.counts, self.workspace, [self.s0, self.s1])
+
+    def backward(self):
+        i = self.inputs
+        B.moe_layer_backward(self.cfg, i["x"], i["dy"], i["Wg"], i["W1"], i["W2"], self.dx, self.dWg, self.dW1,
+                             self.dW2, self.logits, self.topk_idx, self.topk_w, self.slot, self.counts,
+                             self.workspace, [self.s0, self.s1])
+
+    def results(self) -> Dict[str, np.ndarray]:
+        torch.cuda.synchronize(self.device)
+        return dict(y=to_host(self.y), dx=to_host(self.dx), dWg=to_host(self.dWg), dW1=to_host(self.dW1),
+                    dW2=to_host(self.dW2), logits=to_host(self.logits), idx=to_host(self.topk_idx),
+                    w=to_host(self.topk_w), slot=to_host(self.slot), counts=to_host(self.counts))
+
+
+def run_layer_step(shape, inp: Dict[str, np.ndarray], n_partitions=1, reuse=0, poison=True,
+                   second_stream=True, device="cuda:0") -> Dict[str, np.ndarray]:
+    """One step of the HIP path on a synth.MoEShape-like object; returns host arrays."""
+    st = LayerState(shape.T, shape.M, shape.H, shape.E, shape.k, shape.capacity_factor, n_partitions,
+                    shape.dtype, reuse, device, second_stream)
+    st.upload(inp)
+    if poison:
+        st.poison()
+    st.zero_grads()
+    st.step()
+    out = st.results()
+    out["C_p"] = st.C_p
+    return out

@@ -1,0 +1,81 @@
+"""The C-ABI library loads, exports every symbol include/moe.h declares, and its
+host-only entry points (capacity, workspace sizes, argument checks) behave as the
+header says.  No GPU is needed: none of these calls touches the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_22175_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert len(names) >= 16 and "moe_layer_step" in names and "moe_route" in names
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_capacity_matches_the_definition(oracle):
+    for T, E, k, cf, n in [(256, 4, 1, 1.25, 1), (4096, 8, 2, 1.25, 4), (32768, 16, 2, 1.0, 8),
+                           (16384, 16, 2, 2.0, 4), (10, 3, 1, 1.0, 1), (96, 5, 3, 0.7, 4), (64, 7, 2, 1.1, 2)]:
+        cfg = B.make_config(T, 64, 64, E, k, cf, n)
+        assert B.moe_capacity(cfg) == oracle.capacity(T, E, k, cf, n)
+
+
+def test_argument_errors_are_status_codes():
+    ok = B.make_config(256, 64, 128, 4, 1, 1.25, 1, B.MOE_F32)
+    assert B.moe_capacity(ok) == 80
+    bad = [
+        (B.make_config(256, 64, 128, 4, 5, 1.25), 2),          # k > E
+        (B.make_config(256, 64, 128, 4, 1, 1.25, 3), 2),       # T % n != 0
+        (B.make_config(0, 64, 128, 4, 1, 1.25), 2),
+        (B.make_config(256, 64, 128, 4, 1, 0.0), 2),
+        (B.make_config(256, 64, 128, 65, 1, 1.0), 3),          # E > 64
+        (B.make_config(256, 60, 128, 4, 1, 1.0), 3),           # M % 8
+        (B.make_config(256, 64, 128, 4, 1, 1.0, 1, 7), 3),     # dtype
+    ]
+    for cfg, code in bad:
+        with pytest.raises(B.MoEError) as ei:
+            B.moe_capacity(cfg)
+        assert ei.value.status == code
+    # NULL pointers are reported before anything is launched
+    lib = B.lib()
+    assert lib.moe_capacity(ctypes.byref(ok), None) == 1
+    assert lib.moe_route(ctypes.byref(ok), None, None, None, None, None, None, None) == 1
+    assert lib.moe_layer_step(ctypes.byref(ok), *([None] * 18), ctypes.c_size_t(0), None, 2) == 1
+    assert B.status_string(4) == "workspace too small"
+
+
+def test_workspace_follows_the_memory_model(oracle):
+    """saved bytes = the paper's shared-buffer bookkeeping (Section III-D) in elements
+    times the element size, up to 256-byte alignment of each buffer."""
+    T, M, H, E, k, cf = 16384, 1024, 4096, 8, 2, 1.25
+    for n in (1, 2, 4, 8):
+        C_p = oracle.capacity(T, E, k, cf, n)
+        R_p = C_p * E
+        sizes = {}
+        for mode in (0, 1, 2):
+            cfg = B.make_config(T, M, H, E, k, cf, n, B.MOE_BF16, mode)
+            total, saved, temp, routing = B.moe_workspace_bytes(cfg)
+            assert total == saved + temp + routing
+            sizes[mode] = saved
+        assert sizes[0] == 2 * oracle.workspace_model(R_p, n, M, H, 0)
+        # sharing needs at least as many partitions as buffers (Eq. 5 is negative below that)
+        if n >= 2:
+            assert sizes[1] == 2 * oracle.workspace_model(R_p, n, M, H, 1)
+            assert sizes[2] == 2 * oracle.workspace_model(R_p, n, M, H, 2)
+            delta = oracle.paper_memory_model(R_p * n, M, H, E, n)["delta"]
+            assert sizes[0] - sizes[2] == 2 * delta
+        assert sizes[2] <= sizes[1] <= sizes[0] or n == 1

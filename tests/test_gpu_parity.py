@@ -1,0 +1,219 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, on an MI355X.
+
+Integer results (chosen experts, slots, drop masks, counts) and the float32 gate
+logits must match bit for bit; values must agree within
+    max|gpu - ref| / max|ref|  <=  1e-4 (float32)   2e-2 (bf16 storage, float accumulation)
+per tensor.  Every run starts from NaN-poisoned outputs and workspace, so a
+result that was never written, or padding that leaked into a sum, shows up.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_22175_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def relerr(a, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    a = np.asarray(a, dtype=np.float64)
+    assert a.shape == ref.shape
+    assert np.all(np.isfinite(a)), "non-finite values in the GPU result"
+    d = np.abs(a - ref).max()
+    s = np.abs(ref).max()
+    return d / s if s > 0 else d
+
+
+@pytest.fixture(scope="module")
+def runner():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2506_22175_amd import runner as R
+    return R
+
+
+def _oracle(oracle, s, d, n):
+    return oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], s.k, s.capacity_factor, n,
+                             gate_bias=d.get("gate_bias"))
+
+
+def _check_routing(g, r):
+    assert np.array_equal(g["logits"].view(np.uint32), r["logits"].view(np.uint32)), "gate logits differ in bits"
+    assert np.array_equal(g["idx"], r["idx"])
+    assert np.array_equal(g["slot"], r["slot"])
+    assert np.array_equal(g["counts"], r["counts"])
+    assert g["C_p"] == r["C_p"]
+    assert relerr(g["w"], r["w"]) <= 1e-5
+
+
+def _check_values(g, r, tol, names=("y", "dx", "dWg", "dW1", "dW2")):
+    errs = {k: relerr(g[k], r[k]) for k in names}
+    bad = {k: v for k, v in errs.items() if v > tol}
+    assert not bad, f"beyond tolerance {tol}: {bad} (all: {errs})"
+    return errs
+
+
+# ---------------------------------------------------------------------------------
+# whole step, full tensors
+# ---------------------------------------------------------------------------------
+
+def test_tiny_f32_full_parity(oracle, runner):
+    s = synth.WORKLOADS["tiny"]
+    d = synth.make_inputs(s, seed=0)
+    r = _oracle(oracle, s, d, 1)
+    for mode in (0, 1, 2):
+        g = runner.run_layer_step(s, d, 1, mode)
+        _check_routing(g, r)
+        _check_values(g, r, TOL["f32"])
+
+
+@pytest.mark.parametrize("n", [1, 2, 4])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_small_bf16_full_parity(oracle, runner, n, mode):
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=0)
+    r = _oracle(oracle, s, d, n)
+    g = runner.run_layer_step(s, d, n, mode)
+    _check_routing(g, r)
+    _check_values(g, r, TOL["bf16"])
+
+
+CASES = [
+    # name, T, M, H, E, k, cf, dtype, n, zipf
+    ("ragged_f32", 200, 72, 88, 5, 2, 1.0, "f32", 2, None),
+    ("ragged_bf16", 328, 264, 328, 6, 3, 0.9, "bf16", 2, None),
+    ("dense_f32", 96, 64, 128, 1, 1, 1.0, "f32", 1, None),
+    ("dense_bf16", 300, 256, 512, 1, 1, 1.0, "bf16", 1, None),
+    ("k_equals_E_f32", 64, 32, 40, 4, 4, 1.0, "f32", 1, None),
+    ("heavy_drops_bf16", 1024, 128, 256, 4, 2, 0.25, "bf16", 4, None),
+    ("heavy_drops_f32", 512, 64, 64, 4, 2, 0.3, "f32", 2, None),
+    ("many_experts_bf16", 2048, 128, 192, 64, 2, 1.5, "bf16", 2, None),
+    ("many_experts_f32", 512, 64, 64, 33, 8, 1.5, "f32", 1, None),
+    ("skew_empty_experts_bf16", 2048, 256, 256, 16, 2, 2.0, "bf16", 4, 4.0),
+    ("min_dims_f32", 16, 8, 8, 2, 1, 1.0, "f32", 1, None),
+    ("min_dims_bf16", 24, 8, 8, 3, 2, 1.0, "bf16", 3, None),
+    ("one_token_per_partition", 4, 64, 64, 4, 2, 2.0, "f32", 4, None),
+    ("wide_bf16", 512, 1536, 640, 8, 2, 1.25, "bf16", 2, None),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("mode", [0, 2])
+def test_edge_cases_full_parity(oracle, runner, case, mode):
+    name, T, M, H, E, k, cf, dt, n, zipf = case
+    kw = dict(zipf_s=1.2, zipf_tau=zipf) if zipf else {}
+    s = synth.custom_shape(T, M, H, E, k, cf, dtype=dt, x_std=1.0, w_std=0.05, name=name, **kw)
+    d = synth.make_inputs(s, seed=3)
+    r = _oracle(oracle, s, d, n)
+    g = runner.run_layer_step(s, d, n, mode)
+    _check_routing(g, r)
+    _check_values(g, r, TOL[dt])
+    dropped = (r["slot"] < 0).all(axis=1)
+    if dropped.any():                       # fully dropped tokens pass through as exact zeros
+        assert np.all(g["y"][dropped] == 0.0) and np.all(g["dx"][dropped] == 0.0)
+    if name.startswith("heavy_drops") or name.startswith("skew"):
+        assert (r["slot"] < 0).any()
+    if name.startswith("skew"):
+        assert (r["counts"] == 0).any(), "case is meant to leave some expert without rows"
+
+
+def test_results_do_not_depend_on_streams_or_reuse_mode(runner):
+    """Same kernels, same order of accumulation: one stream or two, and the three
+    memory modes, give identical routing and values that agree to rounding."""
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=1)
+    base = runner.run_layer_step(s, d, 4, 0, second_stream=False)
+    for mode, two in ((0, True), (1, True), (2, True), (2, False)):
+        g = runner.run_layer_step(s, d, 4, mode, second_stream=two)
+        for k_ in ("idx", "slot", "counts"):
+            assert np.array_equal(g[k_], base[k_])
+        assert np.array_equal(g["y"], base["y"])                 # forward never differs
+        for k_ in ("dx", "dWg", "dW1", "dW2"):
+            assert relerr(g[k_], base[k_]) <= 1e-2
+    # recomputed T_M is the stored T_M: modes 1 and 2 agree exactly
+    g1 = runner.run_layer_step(s, d, 4, 1)
+    g2 = runner.run_layer_step(s, d, 4, 2)
+    for k_ in ("dx", "dWg", "dW1", "dW2"):
+        assert np.array_equal(g1[k_], g2[k_]), k_
+
+
+def test_repeated_steps_reuse_the_workspace_cleanly(oracle, runner):
+    """Second step on a workspace holding the first step's leftovers; weight
+    gradients accumulate (the caller zeroes them)."""
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=2)
+    st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, 4, s.dtype, 2)
+    st.upload(d)
+    st.poison()
+    st.zero_grads()
+    st.step()
+    a = st.results()
+    st.step()
+    b = st.results()
+    assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["dx"], b["dx"])
+    assert relerr(b["dW1"], 2.0 * a["dW1"]) <= 1e-6
+    assert relerr(b["dWg"], 2.0 * a["dWg"]) <= 1e-6
+
+
+# ---------------------------------------------------------------------------------
+# the large workloads: routing on everything, values on samples
+# ---------------------------------------------------------------------------------
+
+def _sampled_check(oracle, runner, s, n, mode, seed=0, n_tokens=64, n_cols=4):
+    d = synth.make_inputs(s, seed=seed)
+    logits, p, idx, w = oracle.route(d["x"], d["Wg"], s.k, d.get("gate_bias"))
+    C_p = oracle.capacity(s.T, s.E, s.k, s.capacity_factor, n)
+    slot, counts = oracle.assign_slots(idx, s.E, C_p, n)
+    r = dict(logits=logits, idx=idx, w=w, slot=slot, counts=counts, C_p=C_p)
+    g = runner.run_layer_step(s, d, n, mode)
+    _check_routing(g, r)
+    rng = np.random.default_rng(seed + 100)
+    toks = rng.choice(s.T, size=n_tokens, replace=False)
+    dropped = np.nonzero((slot < 0).any(axis=1))[0]
+    if len(dropped):
+        toks = np.concatenate([toks, dropped[:8]])
+    sm = oracle.sampled_tokens(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], r, toks)
+    tol = TOL[s.dtype]
+    ys, dxs = np.abs(sm["y"]).max(), np.abs(sm["dx"]).max()
+    assert np.abs(g["y"][toks] - sm["y"]).max() / ys <= tol
+    assert np.abs(g["dx"][toks] - sm["dx"]).max() / dxs <= tol
+    full = (slot < 0).all(axis=1)
+    if full.any():
+        assert np.all(g["y"][full] == 0.0) and np.all(g["dx"][full] == 0.0)
+    for e in rng.choice(s.E, size=2, replace=False):
+        hc = rng.choice(s.H, size=n_cols, replace=False)
+        mc = rng.choice(s.M, size=n_cols, replace=False)
+        a, b = oracle.sampled_weight_grads(d["x"], d["W1"], d["W2"], d["dy"], r, n, C_p, int(e), hc, mc)
+        assert relerr(g["dW1"][e][:, hc], a) <= tol
+        assert relerr(g["dW2"][e][:, mc], b) <= tol
+    assert np.all(np.isfinite(g["dWg"])) and np.all(np.isfinite(g["dW1"])) and np.all(np.isfinite(g["dW2"]))
+    return g, r
+
+
+def test_gpt_workload_sampled(oracle, runner):
+    _sampled_check(oracle, runner, synth.WORKLOADS["gpt"], 4, 2)
+
+
+def test_gpt_workload_full_oracle_one_partitioning(oracle, runner):
+    s = synth.WORKLOADS["gpt"]
+    d = synth.make_inputs(s, seed=0)
+    r = _oracle(oracle, s, d, 8)
+    g = runner.run_layer_step(s, d, 8, 2)
+    _check_routing(g, r)
+    _check_values(g, r, TOL["bf16"])
+
+
+def test_skewed_workload_sampled(oracle, runner):
+    s = synth.WORKLOADS["skewed"]
+    g, r = _sampled_check(oracle, runner, s, 4, 2)
+    assert (r["slot"] < 0).mean() > 0.1          # the skew really drops tokens
+    assert r["counts"].max() == r["C_p"]         # and fills the popular experts to capacity
+
+
+def test_large_workload_sampled_in_bench_configuration(oracle, runner):
+    """The shape and launch configuration bench.py times."""
+    _sampled_check(oracle, runner, synth.WORKLOADS["large"], 2, 2, n_tokens=48)
