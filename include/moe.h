@@ -195,6 +195,10 @@ moe_status moe_launch_counts(int64_t out[3], int32_t reset);
 
 const char* moe_status_string(moe_status s);
 
+/* Text of the most recent HIP failure behind a MOE_ERR_HIP (HIP's message and the
+ * source line of the failing call); empty if there was none.  Host only. */
+const char* moe_last_error(void);
+
 #ifdef __cplusplus
 }
 #endif

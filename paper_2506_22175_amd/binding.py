@@ -23,13 +23,15 @@ EXPORTS = [
     "moe_dispatch", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_dw_parts", "moe_combine",
     "moe_gate_bwd", "moe_gate_scratch_bytes", "moe_dispatch_bwd", "moe_layer_step",
     "moe_layer_forward", "moe_layer_backward", "moe_launch_counts", "moe_status_string",
+    "moe_last_error",
 ]
 
 
 class MoEError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: status {status} ({status_string(status)})")
+        detail = lib().moe_last_error().decode() if status == 5 else ""
+        super().__init__(f"{where}: status {status} ({status_string(status)}) {detail}")
 
 
 class MoEConfig(ctypes.Structure):
@@ -55,7 +57,7 @@ def lib() -> ctypes.CDLL:
         _lib = ctypes.CDLL(LIB_PATH)
         for name in EXPORTS:
             fn = getattr(_lib, name)
-            fn.restype = ctypes.c_char_p if name == "moe_status_string" else ctypes.c_int
+            fn.restype = ctypes.c_char_p if name in ("moe_status_string", "moe_last_error") else ctypes.c_int
     return _lib
 
 

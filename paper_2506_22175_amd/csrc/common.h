@@ -92,8 +92,12 @@ struct Dims {
 moe_status make_dims(const moe_config* cfg, Dims* d);
 moe_status check_part(const Dims& d, int part);
 
-inline moe_status hip_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
-#define MOE_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP; } while (0)
+// Remembers where a HIP call failed; moe_last_error() returns the text.
+void note_hip_error(hipError_t e, const char* file, int line);
+#define MOE_CHECK_LAUNCH() do { hipError_t _e = hipGetLastError(); \
+    if (_e != hipSuccess) { ::moe::note_hip_error(_e, __FILE__, __LINE__); return MOE_ERR_HIP; } } while (0)
+#define HIP_TRY(expr) do { hipError_t _e = (expr); \
+    if (_e != hipSuccess) { ::moe::note_hip_error(_e, __FILE__, __LINE__); return MOE_ERR_HIP; } } while (0)
 #define MOE_TRY(expr) do { moe_status _s = (expr); if (_s != MOE_OK) return _s; } while (0)
 
 enum LaunchClass { LC_GEMM = 0, LC_PERMUTE = 1, LC_OTHER = 2 };

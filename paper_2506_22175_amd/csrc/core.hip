@@ -2,6 +2,7 @@
 #include "common.h"
 #include <atomic>
 #include <cmath>
+#include <cstdio>
 
 namespace moe {
 
@@ -31,6 +32,11 @@ moe_status check_part(const Dims& d, int part) {
     return (part < 0 || part >= d.n) ? MOE_ERR_SHAPE : MOE_OK;
 }
 
+static char g_last_error[512] = "";
+void note_hip_error(hipError_t e, const char* file, int line) {
+    snprintf(g_last_error, sizeof(g_last_error), "%s (%d) at %s:%d", hipGetErrorString(e), (int)e, file, line);
+}
+
 static std::atomic<long long> g_launches[3];
 void count_launch(LaunchClass c, int n) { g_launches[c].fetch_add(n, std::memory_order_relaxed); }
 
@@ -52,6 +58,8 @@ extern "C" moe_status moe_launch_counts(int64_t out[3], int32_t reset) {
     }
     return MOE_OK;
 }
+
+extern "C" const char* moe_last_error(void) { return moe::g_last_error; }
 
 extern "C" const char* moe_status_string(moe_status s) {
     switch (s) {

@@ -250,8 +250,7 @@ static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
     auto kern = gemm_bf16_kernel<LAY, EPI, BM, BN>;
     static bool attr_done = false;
     if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-            return MOE_ERR_HIP;
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3(nblocks), dim3(G_THREADS), lds, s, a, tiles_m, tiles_n, nblocks);

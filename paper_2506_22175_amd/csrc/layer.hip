@@ -80,7 +80,6 @@ static moe_status get_events(size_t n) {
     }
     return MOE_OK;
 }
-#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return MOE_ERR_HIP; } while (0)
 
 static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace& w, char* ws,
                           const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* W2,

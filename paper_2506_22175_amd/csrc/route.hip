@@ -172,8 +172,8 @@ static moe_status launch_route(const Dims& d, const void* x, const void* Wg, con
     if (MC > ((d.M + 511) / 512) * 512) MC = ((d.M + 511) / 512) * 512;
     size_t lds = ((size_t)MC * EP + (size_t)ROUTE_WAVES * TB * EP) * sizeof(float);
     auto kern = route_kernel<T, EP, TB>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds) != hipSuccess) return MOE_ERR_HIP;
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds));
     int ngroups = (d.T + ROUTE_WAVES * TB - 1) / (ROUTE_WAVES * TB);
     int grid = ngroups < 1024 ? ngroups : 1024;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(ROUTE_THREADS), lds, s,
