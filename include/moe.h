@@ -193,6 +193,19 @@ moe_status moe_layer_backward(const moe_config* cfg, const void* x, const void* 
  * dispatch-backward), out[2] everything else.  Host only. */
 moe_status moe_launch_counts(int64_t out[3], int32_t reset);
 
+/* Optional timing of the library's kernels with HIP events recorded on the
+ * stream each kernel is launched on.  moe_profile_enable(1) clears earlier
+ * records and starts recording; moe_profile_enable(0) stops.  moe_profile_read
+ * waits for the recorded events and returns, per kernel kind, the number of
+ * launches and the summed duration in milliseconds.  Kinds: 0 first FFN GEMM
+ * (GeLU epilogue), 1 second FFN GEMM and recomputation, 2 GEMM with the
+ * GeLU-backward epilogue, 3 input-gradient GEMM, 4 weight-gradient GEMMs,
+ * 5 dispatch, 6 combine, 7 dispatch backward, 8 gate, 9 slot assignment,
+ * 10 gate backward.  Arrays of `kinds` entries (at most 11).  Host only; not
+ * for use under stream capture. */
+moe_status moe_profile_enable(int32_t on);
+moe_status moe_profile_read(int32_t kinds, int64_t* launches, double* total_ms);
+
 const char* moe_status_string(moe_status s);
 
 /* Text of the most recent HIP failure behind a MOE_ERR_HIP (HIP's message and the

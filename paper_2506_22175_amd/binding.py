@@ -23,7 +23,7 @@ EXPORTS = [
     "moe_dispatch", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_dw_parts", "moe_combine",
     "moe_gate_bwd", "moe_gate_scratch_bytes", "moe_dispatch_bwd", "moe_layer_step",
     "moe_layer_forward", "moe_layer_backward", "moe_launch_counts", "moe_status_string",
-    "moe_last_error",
+    "moe_last_error", "moe_profile_enable", "moe_profile_read",
 ]
 
 
@@ -129,6 +129,23 @@ def moe_launch_counts(reset: bool = False):
     arr = (ctypes.c_int64 * 3)()
     _check(lib().moe_launch_counts(arr, ctypes.c_int32(1 if reset else 0)), "moe_launch_counts")
     return tuple(arr)
+
+
+PROFILE_KINDS = ["gemm_fwd1_gelu", "gemm_nn_store", "gemm_dgelu", "gemm_dgrad", "gemm_wgrad", "dispatch",
+                 "combine", "dispatch_bwd", "route", "slots", "gate_bwd"]
+
+
+def moe_profile_enable(on: bool):
+    _check(lib().moe_profile_enable(ctypes.c_int32(1 if on else 0)), "moe_profile_enable")
+
+
+def moe_profile_read():
+    """{kind: (launches, total_ms)} of the kernels timed since moe_profile_enable(True)."""
+    n = len(PROFILE_KINDS)
+    launches = (ctypes.c_int64 * n)()
+    ms = (ctypes.c_double * n)()
+    _check(lib().moe_profile_read(ctypes.c_int32(n), launches, ms), "moe_profile_read")
+    return {PROFILE_KINDS[i]: (int(launches[i]), float(ms[i])) for i in range(n)}
 
 
 # ---- device calls ----------------------------------------------------------------

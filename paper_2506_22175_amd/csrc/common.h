@@ -103,6 +103,23 @@ void note_hip_error(hipError_t e, const char* file, int line);
 enum LaunchClass { LC_GEMM = 0, LC_PERMUTE = 1, LC_OTHER = 2 };
 void count_launch(LaunchClass c, int n = 1);
 
+// Optional per-kernel timing with HIP events on the launching stream (off by
+// default; moe_profile_enable).  Kinds index the table in moe_profile_read.
+enum ProfKind {
+    PK_GEMM_FWD1 = 0,    // T_DI W1 -> gelu            (NN, GeLU epilogue)
+    PK_GEMM_NN = 1,      // A W2 -> T_DO, and the recomputation of T_M (NN, plain store)
+    PK_GEMM_DGELU = 2,   // dDO W2^T with the GeLU-backward epilogue (NT)
+    PK_GEMM_DGRAD = 3,   // dZ W1^T -> dDI                (NT, plain store)
+    PK_GEMM_WGRAD = 4,   // both weight gradients         (TN, float accumulate)
+    PK_DISPATCH = 5, PK_COMBINE = 6, PK_DISPATCH_BWD = 7, PK_ROUTE = 8, PK_SLOTS = 9, PK_GATE_BWD = 10,
+    PK_COUNT = 11
+};
+struct ProfScope {
+    int idx; hipStream_t s;
+    ProfScope(int kind, hipStream_t stream);
+    ~ProfScope();
+};
+
 // ---- grouped GEMM interface (gemm_bf16.hip / gemm_f32.hip) -------------------
 // Three operand layouts, all per expert e with r = counts[e] valid rows:
 //   NN: C[r,N] = A[r,K] * B[K,N]         A rows K-contiguous, B rows N-contiguous
@@ -131,6 +148,13 @@ struct GemmArgs {
     float* dw_part;       // EPI_DGELU: [E*Cp, dw_parts] or NULL
     int dw_parts;
 };
+
+inline int gemm_prof_kind(int lay, int epi) {
+    if (epi == EPI_GELU) return PK_GEMM_FWD1;
+    if (epi == EPI_DGELU) return PK_GEMM_DGELU;
+    if (epi == EPI_ACCUM_F32) return PK_GEMM_WGRAD;
+    return lay == GEMM_NN ? PK_GEMM_NN : PK_GEMM_DGRAD;
+}
 
 moe_status gemm_bf16(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStream_t s);
 moe_status gemm_f32(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStream_t s);

@@ -3,6 +3,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstdio>
+#include <vector>
 
 namespace moe {
 
@@ -40,7 +41,58 @@ void note_hip_error(hipError_t e, const char* file, int line) {
 static std::atomic<long long> g_launches[3];
 void count_launch(LaunchClass c, int n) { g_launches[c].fetch_add(n, std::memory_order_relaxed); }
 
+// ---- optional kernel timing ---------------------------------------------------------
+struct ProfRec { int kind; hipEvent_t a, b; };
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof_recs;      // records of the current session
+static std::vector<hipEvent_t> g_prof_pool;   // timing events, reused across sessions
+static size_t g_prof_pool_used = 0;
+static const size_t PROF_MAX_RECS = 1u << 16;
+
+static bool prof_event(hipEvent_t* e) {
+    if (g_prof_pool_used == g_prof_pool.size()) {
+        hipEvent_t n;
+        if (hipEventCreate(&n) != hipSuccess) return false;
+        g_prof_pool.push_back(n);
+    }
+    *e = g_prof_pool[g_prof_pool_used++];
+    return true;
+}
+
+ProfScope::ProfScope(int kind, hipStream_t stream) : idx(-1), s(stream) {
+    if (!g_prof_on || g_prof_recs.size() >= PROF_MAX_RECS) return;
+    ProfRec r;
+    r.kind = kind;
+    if (!prof_event(&r.a) || !prof_event(&r.b)) return;
+    if (hipEventRecord(r.a, s) != hipSuccess) return;
+    idx = (int)g_prof_recs.size();
+    g_prof_recs.push_back(r);
+}
+ProfScope::~ProfScope() {
+    if (idx >= 0) (void)hipEventRecord(g_prof_recs[idx].b, s);
+}
+
 }  // namespace moe
+
+extern "C" moe_status moe_profile_enable(int32_t on) {
+    moe::g_prof_on = on != 0;
+    if (on) { moe::g_prof_recs.clear(); moe::g_prof_pool_used = 0; }
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_profile_read(int32_t kinds, int64_t* launches, double* total_ms) {
+    if (!launches || !total_ms) return MOE_ERR_NULL;
+    for (int i = 0; i < kinds; ++i) { launches[i] = 0; total_ms[i] = 0.0; }
+    for (const moe::ProfRec& r : moe::g_prof_recs) {
+        if (r.kind >= kinds) continue;
+        HIP_TRY(hipEventSynchronize(r.b));
+        float ms = 0.0f;
+        HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+        launches[r.kind] += 1;
+        total_ms[r.kind] += ms;
+    }
+    return MOE_OK;
+}
 
 extern "C" moe_status moe_capacity(const moe_config* cfg, int32_t* C_p) {
     moe::Dims d;

@@ -253,7 +253,10 @@ static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(nblocks), dim3(G_THREADS), lds, s, a, tiles_m, tiles_n, nblocks);
+    {
+        ProfScope ps(gemm_prof_kind(LAY, EPI), s);
+        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(G_THREADS), lds, s, a, tiles_m, tiles_n, nblocks);
+    }
     count_launch(LC_GEMM);
     MOE_CHECK_LAUNCH();
     return MOE_OK;

@@ -94,6 +94,7 @@ static moe_status launch_f32(GemmEpilogue epi, const GemmArgs& a, hipStream_t s)
     const int Mmax = (LAY == GEMM_TN) ? a.Mo : a.Cp;
     const int tiles_m = (Mmax + F_BM - 1) / F_BM, tiles_n = (a.N + F_BN - 1) / F_BN;
     dim3 grid(tiles_n, tiles_m, a.E), block(F_THREADS);
+    ProfScope ps(gemm_prof_kind(LAY, epi), s);
     switch (epi) {
         case EPI_STORE: hipLaunchKernelGGL((gemm_f32_kernel<LAY, EPI_STORE>), grid, block, 0, s, a, tiles_m, tiles_n); break;
         case EPI_GELU: hipLaunchKernelGGL((gemm_f32_kernel<LAY, EPI_GELU>), grid, block, 0, s, a, tiles_m, tiles_n); break;

@@ -240,6 +240,7 @@ template <typename T>
 static moe_status dispatch_t(const Dims& d, int part, const void* src, const int* slot, void* DI,
                              const void* saved, float* dw, hipStream_t s) {
     dim3 grid((d.Tp + PERM_WAVES - 1) / PERM_WAVES);
+    ProfScope ps(PK_DISPATCH, s);
     if (saved && dw)
         hipLaunchKernelGGL((dispatch_kernel<T, true>), grid, dim3(PERM_THREADS), 0, s, (const T*)src, slot,
                            (T*)DI, (const T*)saved, dw, part * d.Tp, d.Tp, d.M, d.k);
@@ -257,6 +258,7 @@ static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const
     dim3 grid((d.M / 8 + PERM_THREADS - 1) / PERM_THREADS, (d.Tp + DXB_TOK - 1) / DXB_TOK);
 #define LAUNCH_DXB(EC) hipLaunchKernelGGL((dispatch_bwd_kernel<T, EC>), grid, dim3(PERM_THREADS), 0, s, \
         (const T*)dDI, slot, dL, (const T*)Wg, (T*)dx, part * d.Tp, d.Tp, d.M, d.E, d.k)
+    ProfScope ps(PK_DISPATCH_BWD, s);
     if (d.E <= 4) LAUNCH_DXB(4);
     else if (d.E <= 8) LAUNCH_DXB(8);
     else LAUNCH_DXB(16);
@@ -270,6 +272,7 @@ template <typename T>
 static moe_status gate_bwd_t(const Dims& d, int part, const void* x, const float* logits, const int* idx,
                              const int* slot, const float* dw, const float* dw_part, int parts,
                              float* dL, float* dWg, void* scratch, hipStream_t s) {
+    ProfScope ps(PK_GATE_BWD, s);
     hipLaunchKernelGGL(gate_dl_kernel, dim3((d.Tp + 255) / 256), dim3(256), 0, s, logits, idx, slot, dw,
                        dw_part, parts, dL, part * d.Tp, d.Tp, d.E, d.k);
     MOE_CHECK_LAUNCH();
@@ -308,6 +311,7 @@ extern "C" moe_status moe_combine(const moe_config* cfg, int32_t part, const voi
     if (!DO || !slot || !topk_w || !y) return MOE_ERR_NULL;
     dim3 grid((d.Tp + PERM_WAVES - 1) / PERM_WAVES);
     hipStream_t s = (hipStream_t)stream;
+    ProfScope ps(PK_COMBINE, s);
     if (d.dtype == MOE_F32)
         hipLaunchKernelGGL((combine_kernel<float>), grid, dim3(PERM_THREADS), 0, s, (const float*)DO, slot,
                            topk_w, (float*)y, part * d.Tp, d.Tp, d.M, d.k);

@@ -176,6 +176,7 @@ static moe_status launch_route(const Dims& d, const void* x, const void* Wg, con
                             (int)lds));
     int ngroups = (d.T + ROUTE_WAVES * TB - 1) / (ROUTE_WAVES * TB);
     int grid = ngroups < 1024 ? ngroups : 1024;
+    ProfScope ps(PK_ROUTE, s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(ROUTE_THREADS), lds, s,
                        (const T*)x, (const T*)Wg, bias, logits, idx, w, d.T, d.M, d.E, d.k, MC);
     count_launch(LC_OTHER);

@@ -90,6 +90,7 @@ extern "C" moe_status moe_assign_slots(const moe_config* cfg, const int32_t* top
     hipStream_t s = (hipStream_t)stream;
     int nb = (d.Tp + moe::SLOT_BLOCK - 1) / moe::SLOT_BLOCK;
     dim3 grid(nb, d.k, d.n);
+    moe::ProfScope ps(moe::PK_SLOTS, s);
     hipLaunchKernelGGL(moe::slot_hist_kernel, grid, dim3(moe::SLOT_BLOCK), 0, s,
                        topk_idx, (int*)scratch, d.Tp, d.k, d.E, nb);
     MOE_CHECK_LAUNCH();
