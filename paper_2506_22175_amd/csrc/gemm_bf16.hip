@@ -22,21 +22,36 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int G_BK = 64;
-constexpr int G_THREADS = 256;
 constexpr int G_ROWB = G_BK * 2;          // bytes of one LDS tile row
 
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
-// ---- global -> registers --------------------------------------------------------
+// ---- tile shape ------------------------------------------------------------------
+// BM x BN output tile, WAVES_M x WAVES_N wavefronts, STAGES LDS buffers (2: the
+// next tile is written while this one is multiplied; 1: write after a barrier,
+// with a second workgroup on the CU covering the gap), OCC wavefronts per SIMD.
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int STAGES_, int OCC_>
+struct TileCfg {
+    static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+    static constexpr int STAGES = STAGES_, OCC = OCC_;
+    static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int TM = WM / 32, TN = WN / 32;
+    static constexpr int STAGE_BYTES = (BM + BN) * G_ROWB;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+};
+
+// ---- global -> registers -> LDS -----------------------------------------------------
 // Direct: operand rows are K-contiguous.  R rows x 64 K = R*8 chunks of 16 bytes.
-template <int R>
+template <int R, int THREADS>
 struct DirectTile {
-    static constexpr int N = R * 8 / G_THREADS;
+    static constexpr int N = R * 8 / THREADS;
+    static_assert(R * 8 % THREADS == 0, "tile rows must divide over the threads");
     uint4 v[N];
     __device__ __forceinline__ void load(const bf16_t* P, int ld, int row0, int row_limit, int k0, int K, int tid) {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const int q = tid + i * G_THREADS;
+            const int q = tid + i * THREADS;
             const int row = q >> 3, c = q & 7;
             const int gr = row0 + row, gk = k0 + c * 8;
             if (gr < row_limit && gk < K)
@@ -48,60 +63,72 @@ struct DirectTile {
     __device__ __forceinline__ void store(char* lds, int tid) const {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const int q = tid + i * G_THREADS;
+            const int q = tid + i * THREADS;
             const int row = q >> 3, c = q & 7;
             *reinterpret_cast<uint4*>(lds + row * G_ROWB + ((c ^ swz(row)) << 4)) = v[i];
         }
     }
 };
 
-// Transposed: operand is [k][n] with n contiguous.  A thread takes an 8(k) x 8(n)
-// block, transposes it in registers and writes eight K-contiguous chunks.
-template <int R>
+// Transposed: operand is [k][n] with n contiguous.  A thread takes a KR(k) x 8(n)
+// block (KR = 8 or 4), transposes it in registers and writes eight K-contiguous
+// pieces of KR elements.
+template <int R, int THREADS>
 struct TransTile {
     static constexpr int NG = R / 8;                  // n-groups per tile
-    uint4 v[8];
+    static constexpr int KR = 64 * NG / THREADS >= 1 ? 8 / ((THREADS + 8 * NG - 1) / (8 * NG)) : 8;
+    static_assert(KR == 8 || KR == 4, "a thread transposes 8 or 4 K-rows");
+    static constexpr int UNITS = NG * (64 / KR);      // threads that carry a block
+    uint4 v[KR];
     __device__ __forceinline__ void load(const bf16_t* P, int ld, int n0, int n_limit, int k0, int K, int tid) {
         const int ng = tid % NG, kg = tid / NG;
         const int gn = n0 + ng * 8;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int gk = k0 + kg * 8 + j;
-            if (tid < R && gn < n_limit && gk < K)
+        for (int j = 0; j < KR; ++j) {
+            const int gk = k0 + kg * KR + j;
+            if (tid < UNITS && gn < n_limit && gk < K)
                 v[j] = *reinterpret_cast<const uint4*>(P + (size_t)gk * ld + gn);
             else
                 v[j] = make_uint4(0, 0, 0, 0);
         }
     }
     __device__ __forceinline__ void store(char* lds, int tid) const {
-        if (tid >= R) return;
+        if (tid >= UNITS) return;
         const int ng = tid % NG, kg = tid / NG;
         const unsigned* w = reinterpret_cast<const unsigned*>(v);   // w[j*4 + q]
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int q = i >> 1;
             const unsigned sel = (i & 1) ? 0x07060302u : 0x05040100u;
-            uint4 o;
-            o.x = __builtin_amdgcn_perm(w[1 * 4 + q], w[0 * 4 + q], sel);
-            o.y = __builtin_amdgcn_perm(w[3 * 4 + q], w[2 * 4 + q], sel);
-            o.z = __builtin_amdgcn_perm(w[5 * 4 + q], w[4 * 4 + q], sel);
-            o.w = __builtin_amdgcn_perm(w[7 * 4 + q], w[6 * 4 + q], sel);
             const int row = ng * 8 + i;
-            *reinterpret_cast<uint4*>(lds + row * G_ROWB + ((kg ^ swz(row)) << 4)) = o;
+            if constexpr (KR == 8) {
+                uint4 o;
+                o.x = __builtin_amdgcn_perm(w[1 * 4 + q], w[0 * 4 + q], sel);
+                o.y = __builtin_amdgcn_perm(w[3 * 4 + q], w[2 * 4 + q], sel);
+                o.z = __builtin_amdgcn_perm(w[5 * 4 + q], w[4 * 4 + q], sel);
+                o.w = __builtin_amdgcn_perm(w[7 * 4 + q], w[6 * 4 + q], sel);
+                *reinterpret_cast<uint4*>(lds + row * G_ROWB + ((kg ^ swz(row)) << 4)) = o;
+            } else {
+                uint2 o;
+                o.x = __builtin_amdgcn_perm(w[1 * 4 + q], w[0 * 4 + q], sel);
+                o.y = __builtin_amdgcn_perm(w[3 * 4 + q], w[2 * 4 + q], sel);
+                *reinterpret_cast<uint2*>(lds + row * G_ROWB + (((kg >> 1) ^ swz(row)) << 4) + ((kg & 1) << 3)) = o;
+            }
         }
     }
 };
 
-template <int LAY, int BM> struct ATile { typedef DirectTile<BM> type; };
-template <int BM> struct ATile<GEMM_TN, BM> { typedef TransTile<BM> type; };
-template <int LAY, int BN> struct BTile { typedef TransTile<BN> type; };
-template <int BN> struct BTile<GEMM_NT, BN> { typedef DirectTile<BN> type; };
+template <int LAY, int R, int T> struct ATile { typedef DirectTile<R, T> type; };
+template <int R, int T> struct ATile<GEMM_TN, R, T> { typedef TransTile<R, T> type; };
+template <int LAY, int R, int T> struct BTile { typedef TransTile<R, T> type; };
+template <int R, int T> struct BTile<GEMM_NT, R, T> { typedef DirectTile<R, T> type; };
 
-template <int LAY, int EPI, int BM, int BN>
-__global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
+template <int LAY, int EPI, typename C>
+__global__ __launch_bounds__(C::THREADS) __attribute__((amdgpu_waves_per_eu(C::OCC, C::OCC)))
+void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TNN = WN / 32;
-    constexpr int STAGE = (BM + BN) * G_ROWB;
+    constexpr int BM = C::BM, BN = C::BN, WM = C::WM, WN = C::WN, TM = C::TM, TNN = C::TN;
+    constexpr int STAGE = C::STAGE_BYTES;
 
     // ---- workgroup -> (expert, tile) with XCD-aware order ------------------------
     // Hardware deals consecutive workgroup ids round-robin to the 8 XCDs; give each
@@ -136,10 +163,10 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(GemmArgs g, int ti
     const bf16_t* A = (const bf16_t*)g.A + (size_t)e * g.a_estride;
     const bf16_t* B = (const bf16_t*)g.B + (size_t)e * g.b_estride;
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
-    const int wm = wid >> 1, wn = wid & 1;
+    const int wm = wid / C::WAVES_N, wn = wid % C::WAVES_N;
 
-    typename ATile<LAY, BM>::type ta;
-    typename BTile<LAY, BN>::type tb;
+    typename ATile<LAY, BM, C::THREADS>::type ta;
+    typename BTile<LAY, BN, C::THREADS>::type tb;
     const int KT = (Kdim + G_BK - 1) / G_BK;
 
     auto load_tiles = [&](int kt) {
@@ -175,16 +202,7 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(GemmArgs g, int ti
     }
     const int khalf = lane >> 5;
 
-    load_tiles(0);
-    store_tiles(0);
-    if (KT > 1) load_tiles(1);
-    __syncthreads();
-
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) store_tiles(cur ^ 1);
-        if (kt + 2 < KT) load_tiles(kt + 2);
-        const char* base = smem + cur * STAGE;
+    auto compute = [&](const char* base) {
 #pragma unroll
         for (int kk = 0; kk < G_BK / 16; ++kk) {
             bf16x8 af[TM], bfr[TNN];
@@ -201,7 +219,29 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(GemmArgs g, int ti
                 for (int j = 0; j < TNN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
+    };
+
+    if constexpr (C::STAGES == 2) {
+        load_tiles(0);
+        store_tiles(0);
+        if (KT > 1) load_tiles(1);
         __syncthreads();
+        for (int kt = 0; kt < KT; ++kt) {
+            const int cur = kt & 1;
+            if (kt + 1 < KT) store_tiles(cur ^ 1);
+            if (kt + 2 < KT) load_tiles(kt + 2);
+            compute(smem + cur * STAGE);
+            __syncthreads();
+        }
+    } else {
+        load_tiles(0);
+        for (int kt = 0; kt < KT; ++kt) {
+            store_tiles(0);
+            __syncthreads();
+            if (kt + 1 < KT) load_tiles(kt + 1);
+            compute(smem);
+            __syncthreads();
+        }
     }
 
     // ---- epilogue: lane holds row m = (lane & 31), columns 8*g4 + 4*(lane>>5) + 0..3 ----
@@ -232,22 +272,36 @@ __global__ __launch_bounds__(G_THREADS) void gemm_bf16_kernel(GemmArgs g, int ti
         }
         if (EPI == EPI_DGELU && g.dw_part) {
             dot += __shfl_xor(dot, 32, 64);
-            if (elane < 32 && m < Mdim) g.dw_part[((size_t)e * g.Cp + m) * g.dw_parts + tn * 2 + wn] = dot;
+            if (elane < 32 && m < Mdim)
+                g.dw_part[((size_t)e * g.Cp + m) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
         }
     }
 }
 
-constexpr int DEF_BM = 256, DEF_BN = 256;
-int gemm_bf16_dw_parts(int H) { return ((H + DEF_BN - 1) / DEF_BN) * 2; }
+// Tile shape in use.  MOE_GEMM_CFG selects it at build time for experiments.
+#ifndef MOE_GEMM_CFG
+#define MOE_GEMM_CFG 0
+#endif
+#if MOE_GEMM_CFG == 0
+typedef TileCfg<256, 256, 2, 2, 2, 1> Cfg;     // 4 waves of 128x128, double-buffered LDS
+#elif MOE_GEMM_CFG == 1
+typedef TileCfg<128, 256, 2, 2, 1, 2> Cfg;     // 4 waves of 64x128, two workgroups per CU
+#elif MOE_GEMM_CFG == 2
+typedef TileCfg<256, 256, 2, 4, 2, 2> Cfg;     // 8 waves of 128x64, double-buffered LDS
+#elif MOE_GEMM_CFG == 3
+typedef TileCfg<256, 128, 2, 2, 1, 2> Cfg;     // 4 waves of 128x64, two workgroups per CU
+#endif
 
-template <int LAY, int EPI, int BM, int BN>
+int gemm_bf16_dw_parts(int H) { return ((H + Cfg::BN - 1) / Cfg::BN) * Cfg::WAVES_N; }
+
+template <int LAY, int EPI, typename C>
 static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
     const int Mmax = (LAY == GEMM_TN) ? a.Mo : a.Cp;
-    const int tiles_m = (Mmax + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+    const int tiles_m = (Mmax + C::BM - 1) / C::BM, tiles_n = (a.N + C::BN - 1) / C::BN;
     int nblocks = a.E * tiles_m * tiles_n;
     nblocks = (nblocks + 7) / 8 * 8;
-    constexpr int lds = 2 * (BM + BN) * G_ROWB;
-    auto kern = gemm_bf16_kernel<LAY, EPI, BM, BN>;
+    constexpr int lds = C::LDS_BYTES;
+    auto kern = gemm_bf16_kernel<LAY, EPI, C>;
     static bool attr_done = false;
     if (!attr_done) {
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
@@ -255,7 +309,7 @@ static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
     }
     {
         ProfScope ps(gemm_prof_kind(LAY, EPI), s);
-        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(G_THREADS), lds, s, a, tiles_m, tiles_n, nblocks);
+        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(C::THREADS), lds, s, a, tiles_m, tiles_n, nblocks);
     }
     count_launch(LC_GEMM);
     MOE_CHECK_LAUNCH();
@@ -265,10 +319,10 @@ static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
 template <int LAY>
 static moe_status launch_lay(GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
     switch (epi) {
-        case EPI_STORE: return launch_one<LAY, EPI_STORE, DEF_BM, DEF_BN>(a, s);
-        case EPI_GELU: return launch_one<LAY, EPI_GELU, DEF_BM, DEF_BN>(a, s);
-        case EPI_DGELU: return launch_one<LAY, EPI_DGELU, DEF_BM, DEF_BN>(a, s);
-        case EPI_ACCUM_F32: return launch_one<LAY, EPI_ACCUM_F32, DEF_BM, DEF_BN>(a, s);
+        case EPI_STORE: return launch_one<LAY, EPI_STORE, Cfg>(a, s);
+        case EPI_GELU: return launch_one<LAY, EPI_GELU, Cfg>(a, s);
+        case EPI_DGELU: return launch_one<LAY, EPI_DGELU, Cfg>(a, s);
+        case EPI_ACCUM_F32: return launch_one<LAY, EPI_ACCUM_F32, Cfg>(a, s);
     }
     return MOE_ERR_UNSUPPORTED;
 }
