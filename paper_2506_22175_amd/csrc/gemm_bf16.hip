@@ -42,22 +42,42 @@ struct TileCfg {
 };
 
 // ---- global -> registers -> LDS -----------------------------------------------------
+// Global reads go through buffer descriptors that cover exactly the valid rows
+// of the operand, so out-of-range rows read as zero in hardware and the loop has
+// no branches; a K tail or a column beyond the matrix is turned into an
+// out-of-range offset by a select.
+typedef int v4i __attribute__((ext_vector_type(4)));
+constexpr unsigned OOB_OFFSET = 0x80000000u;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, unsigned off) {
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
+}
+
 // Direct: operand rows are K-contiguous.  R rows x 64 K = R*8 chunks of 16 bytes.
+// The descriptor starts at the tile's first row and ends after its last valid row.
 template <int R, int THREADS>
 struct DirectTile {
     static constexpr int N = R * 8 / THREADS;
     static_assert(R * 8 % THREADS == 0, "tile rows must divide over the threads");
     uint4 v[N];
-    __device__ __forceinline__ void load(const bf16_t* P, int ld, int row0, int row_limit, int k0, int K, int tid) {
+    __amdgpu_buffer_rsrc_t rsrc;
+    int ld;
+    __device__ __forceinline__ void init(const bf16_t* P, int ld_, int row0, int row_limit, int /*col0*/, int /*col_limit*/, int K) {
+        const int valid = min(R, row_limit - row0);
+        ld = ld_;
+        rsrc = make_rsrc(P + (size_t)row0 * ld_, (unsigned)(((size_t)(valid - 1) * ld_ + K) * 2));
+    }
+    __device__ __forceinline__ void load(int k0, int K, int tid) {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const int q = tid + i * THREADS;
             const int row = q >> 3, c = q & 7;
-            const int gr = row0 + row, gk = k0 + c * 8;
-            if (gr < row_limit && gk < K)
-                v[i] = *reinterpret_cast<const uint4*>(P + (size_t)gr * ld + gk);
-            else
-                v[i] = make_uint4(0, 0, 0, 0);
+            const int gk = k0 + c * 8;
+            const unsigned off = (unsigned)(row * ld + gk) * 2u;
+            v[i] = buffer_load16(rsrc, gk < K ? off : OOB_OFFSET);
         }
     }
     __device__ __forceinline__ void store(char* lds, int tid) const {
@@ -72,24 +92,30 @@ struct DirectTile {
 
 // Transposed: operand is [k][n] with n contiguous.  A thread takes a KR(k) x 8(n)
 // block (KR = 8 or 4), transposes it in registers and writes eight K-contiguous
-// pieces of KR elements.
+// pieces of KR elements.  The descriptor starts at the tile's first column and
+// ends after the last valid K row.
 template <int R, int THREADS>
 struct TransTile {
     static constexpr int NG = R / 8;                  // n-groups per tile
-    static constexpr int KR = 64 * NG / THREADS >= 1 ? 8 / ((THREADS + 8 * NG - 1) / (8 * NG)) : 8;
-    static_assert(KR == 8 || KR == 4, "a thread transposes 8 or 4 K-rows");
+    static constexpr int KR = (THREADS >= 16 * NG) ? 4 : 8;
+    static_assert(THREADS >= 64 * NG / KR, "not enough threads for the tile");
     static constexpr int UNITS = NG * (64 / KR);      // threads that carry a block
     uint4 v[KR];
-    __device__ __forceinline__ void load(const bf16_t* P, int ld, int n0, int n_limit, int k0, int K, int tid) {
+    __amdgpu_buffer_rsrc_t rsrc;
+    int ld, n_valid;
+    __device__ __forceinline__ void init(const bf16_t* P, int ld_, int n0, int n_limit, int /*k0*/, int /*unused*/, int K) {
+        ld = ld_;
+        n_valid = n_limit - n0;
+        rsrc = make_rsrc(P + n0, (unsigned)(((size_t)(K - 1) * ld_ + n_valid) * 2));
+    }
+    __device__ __forceinline__ void load(int k0, int /*K*/, int tid) {
         const int ng = tid % NG, kg = tid / NG;
-        const int gn = n0 + ng * 8;
+        const bool on = tid < UNITS && ng * 8 < n_valid;
 #pragma unroll
         for (int j = 0; j < KR; ++j) {
             const int gk = k0 + kg * KR + j;
-            if (tid < UNITS && gn < n_limit && gk < K)
-                v[j] = *reinterpret_cast<const uint4*>(P + (size_t)gk * ld + gn);
-            else
-                v[j] = make_uint4(0, 0, 0, 0);
+            const unsigned off = (unsigned)(gk * ld + ng * 8) * 2u;
+            v[j] = buffer_load16(rsrc, on ? off : OOB_OFFSET);
         }
     }
     __device__ __forceinline__ void store(char* lds, int tid) const {
@@ -169,9 +195,11 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     typename BTile<LAY, BN, C::THREADS>::type tb;
     const int KT = (Kdim + G_BK - 1) / G_BK;
 
+    ta.init(A, g.lda, m0, Mdim, 0, 0, Kdim);
+    tb.init(B, g.ldb, n0, g.N, 0, 0, Kdim);
     auto load_tiles = [&](int kt) {
-        ta.load(A, g.lda, m0, Mdim, kt * G_BK, Kdim, tid);
-        tb.load(B, g.ldb, n0, g.N, kt * G_BK, Kdim, tid);
+        ta.load(kt * G_BK, Kdim, tid);
+        tb.load(kt * G_BK, Kdim, tid);
     };
     auto store_tiles = [&](int stage) {
         ta.store(smem + stage * STAGE, tid);
@@ -224,13 +252,29 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     if constexpr (C::STAGES == 2) {
         load_tiles(0);
         store_tiles(0);
-        if (KT > 1) load_tiles(1);
+        load_tiles(1);                       // tiles past the end read as zeros
         __syncthreads();
         for (int kt = 0; kt < KT; ++kt) {
             const int cur = kt & 1;
-            if (kt + 1 < KT) store_tiles(cur ^ 1);
-            if (kt + 2 < KT) load_tiles(kt + 2);
+            // One straight-line block per iteration: write tile kt+1 into the other
+            // LDS buffer, start the global reads of tile kt+2, multiply tile kt.
+            store_tiles(cur ^ 1);
+            load_tiles(kt + 2);
             compute(smem + cur * STAGE);
+            // Issue order for the block: the first fragments, then the matrix
+            // instructions with LDS reads, LDS writes and global reads between them,
+            // so the matrix pipe stays busy while the memory pipes work.
+            constexpr int NMFMA = TM * TNN * (G_BK / 16);
+            constexpr int NDSR = (TM + TNN) * (G_BK / 16);
+            constexpr int FIRST = TM + TNN;
+            __builtin_amdgcn_sched_group_barrier(0x100, FIRST, 0);
+#pragma unroll
+            for (int i = 0; i < NMFMA; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (i < NDSR - FIRST) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (i % 2 == 0) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                if (i % 2 == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
             __syncthreads();
         }
     } else {
@@ -280,7 +324,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
 
 // Tile shape in use.  MOE_GEMM_CFG selects it at build time for experiments.
 #ifndef MOE_GEMM_CFG
-#define MOE_GEMM_CFG 0
+#define MOE_GEMM_CFG 2
 #endif
 #if MOE_GEMM_CFG == 0
 typedef TileCfg<256, 256, 2, 2, 2, 1> Cfg;     // 4 waves of 128x128, double-buffered LDS
