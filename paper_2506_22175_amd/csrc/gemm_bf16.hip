@@ -3,16 +3,27 @@
 // (Table II counts 2 forward and 4 backward GEMM units per partition, 5 with
 // recomputation).  Float accumulation in v_mfma_f32_32x32x16_bf16.
 //
-// One workgroup (4 wavefronts, 2x2) computes a BM x BN tile of one expert; each
-// wavefront owns (BM/2) x (BN/2) as 32x32 MFMA tiles.  Both operands are staged
-// in LDS with K contiguous (64 K-elements = one 128-byte row per tile row) and a
-// 16-byte-chunk XOR swizzle, so fragment reads are conflict-free ds_read_b128.
-// Operands whose K index is the slow one in memory (B of NN, both of TN) are
-// transposed in registers (8x8 blocks, v_perm_b32) on their way into LDS, which
-// keeps one MFMA loop for all three layouts.  LDS is double buffered and the
-// global loads for tile k+2 are in flight while tile k is multiplied.
-// Workgroup ids are remapped so that the workgroups resident on one XCD share
-// A/B panels through that XCD's L2.
+// One workgroup computes a BM x BN tile of one expert with WAVES_M x WAVES_N
+// wavefronts, each owning (BM/WAVES_M) x (BN/WAVES_N) as 32x32 MFMA tiles.
+//
+// Operand tiles (64 K-elements deep) travel global -> LDS with
+// buffer_load_dwordx4 ... lds: no staging registers, no LDS-write instructions,
+// and rows beyond the valid range read as zeros in hardware (the buffer
+// descriptor ends after the last valid row), so the main loop has no branches.
+// Each lane of such a load lands at LDS base + 16*lane, so the LDS layout is
+// chosen by choosing which 16 global bytes each lane fetches:
+//   * an operand whose rows are K-contiguous in memory ("KC": A of NN/NT, B of
+//     NT) is kept as [row][64 k] with a 16-byte-chunk XOR swizzle and read with
+//     ds_read_b128 - conflict-free both ways;
+//   * an operand stored [k][n] with n contiguous ("NC": B of NN, both of TN) is
+//     kept as it is, rows rotated by 64 bytes per k mod 4, and read with
+//     ds_read_b64_tr_b16, which hands each lane four consecutive k of one n.
+// LDS is a ring of NS stages of BK K-elements each; the loads of the next NS-1
+// tiles are in flight while one tile is multiplied (a CU draws about 64 KB per
+// microsecond at speed and a miss in L2 takes longer than one tile's arithmetic,
+// so the depth of the ring, not the hit rate, decides whether the matrix pipe
+// waits).  One s_barrier per tile.  Workgroup ids are remapped so that the
+// workgroups resident on one XCD share A/B panels through that XCD's L2.
 #include "common.h"
 #include "epilogue.h"
 
@@ -20,141 +31,183 @@ namespace moe {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4s lds_v4s;
 
-constexpr int G_BK = 64;
-constexpr int G_ROWB = G_BK * 2;          // bytes of one LDS tile row
-
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
-
-// ---- tile shape ------------------------------------------------------------------
-// BM x BN output tile, WAVES_M x WAVES_N wavefronts, STAGES LDS buffers (2: the
-// next tile is written while this one is multiplied; 1: write after a barrier,
-// with a second workgroup on the CU covering the gap), OCC wavefronts per SIMD.
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int STAGES_, int OCC_>
-struct TileCfg {
-    static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
-    static constexpr int STAGES = STAGES_, OCC = OCC_;
-    static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
-    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
-    static constexpr int TM = WM / 32, TN = WN / 32;
-    static constexpr int STAGE_BYTES = (BM + BN) * G_ROWB;
-    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
-};
-
-// ---- global -> registers -> LDS -----------------------------------------------------
-// Global reads go through buffer descriptors that cover exactly the valid rows
-// of the operand, so out-of-range rows read as zero in hardware and the loop has
-// no branches; a K tail or a column beyond the matrix is turned into an
-// out-of-range offset by a select.
-typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr unsigned OOB_OFFSET = 0x80000000u;
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+// Buffer descriptor (base, stride 0, size in bytes, raw 32-bit format) kept in SGPRs.
+typedef int v4i __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ v4i make_rsrc(const void* p, unsigned bytes) {
+    const unsigned long long a = (unsigned long long)p;
+    v4i d = {(int)(unsigned)a, (int)((a >> 32) & 0xffffu), (int)bytes, 0x00020000};
+    return d;
 }
-__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, unsigned off) {
-    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
+// 16 bytes per lane from the buffer straight into LDS at lds_off + 16*lane (lds_off is a
+// wave-uniform LDS byte address).  Written as assembly so that the compiler's
+// wait-count bookkeeping does not see an LDS store in flight: it would otherwise make
+// every transposing LDS read wait for all of them (vmcnt(0)), which serialises the
+// ring.  The kernel waits with explicit s_waitcnt vmcnt(N) before each barrier instead.
+__device__ __forceinline__ void load_to_lds(v4i rsrc, unsigned lds_off, unsigned voff) {
+    unsigned saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\t"
+                 "s_mov_b32 m0, %1\n\t"
+                 "s_nop 0\n\t"
+                 "buffer_load_dwordx4 %2, %3, 0 offen lds\n\t"
+                 "s_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "s"(lds_off), "v"(voff), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ unsigned lds_address(const char* p) {
+    return (unsigned)(unsigned long long)(__attribute__((address_space(3))) const char*)p;
 }
 
-// Direct: operand rows are K-contiguous.  R rows x 64 K = R*8 chunks of 16 bytes.
-// The descriptor starts at the tile's first row and ends after its last valid row.
-template <int R, int THREADS>
-struct DirectTile {
-    static constexpr int N = R * 8 / THREADS;
-    static_assert(R * 8 % THREADS == 0, "tile rows must divide over the threads");
-    uint4 v[N];
-    __amdgpu_buffer_rsrc_t rsrc;
-    int ld;
-    __device__ __forceinline__ void init(const bf16_t* P, int ld_, int row0, int row_limit, int /*col0*/, int /*col_limit*/, int K) {
+// ---- tile shape ------------------------------------------------------------------
+template <int BM_, int BN_, int BK_, int NS_, int WAVES_M_, int WAVES_N_, int OCC_>
+struct TileCfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, NS = NS_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+    static constexpr int OCC = OCC_;
+    static constexpr int WAVES = WAVES_M * WAVES_N;
+    static constexpr int THREADS = 64 * WAVES;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int TM = WM / 32, TN = WN / 32;
+    static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
+    static constexpr int LDS_BYTES = NS * STAGE_BYTES;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds the CU's 160 KB");
+    static_assert(BK == 32 || BK == 64, "tile depth");
+};
+
+// ---- K-contiguous operand tile: R rows x BK k ---------------------------------------
+// A row is CPR = BK/8 chunks of 16 bytes.  LDS byte of (row, chunk c) =
+// row*ROWB + ((c ^ sw(row)) << 4), with sw chosen so that the 16 rows one
+// ds_read_b128 quarter-wave touches fall into 16 different 16-byte bank groups
+// (64 banks of 4 bytes).  One wave instruction fills 1024 bytes = RPI rows:
+// lane l -> row RPI*q + l/CPR, physical chunk l%CPR.
+template <int R, int WAVES, int BK>
+struct KCTile {
+    static constexpr int ROWB = BK * 2;
+    static constexpr int CPR = BK / 8;
+    static constexpr int RPI = 1024 / ROWB;
+    static constexpr int NI = R / RPI / WAVES;         // load instructions per wave per tile
+    static constexpr int BYTES = R * ROWB;
+    static_assert(R % (RPI * WAVES) == 0 && NI >= 1, "rows must divide over the wavefronts");
+    static __device__ __forceinline__ int sw(int row) {
+        return CPR == 8 ? ((row ^ (row >> 3)) & 7) : ((row >> 2) & 3);
+    }
+    v4i rsrc;
+    unsigned voff[NI];       // byte offset of this lane's chunk at k0 = 0
+    int kc[NI];              // first k of this lane's chunk
+    int K;
+    // P: operand base of this expert; rows [row0, row_limit) x [0, K) are valid
+    __device__ __forceinline__ void init(const bf16_t* P, int ld, int row0, int row_limit, int K_, int lane, int wid) {
         const int valid = min(R, row_limit - row0);
-        ld = ld_;
-        rsrc = make_rsrc(P + (size_t)row0 * ld_, (unsigned)(((size_t)(valid - 1) * ld_ + K) * 2));
-    }
-    __device__ __forceinline__ void load(int k0, int K, int tid) {
+        K = K_;
+        rsrc = make_rsrc(P + (size_t)row0 * ld, (unsigned)(((size_t)(valid - 1) * ld + K_) * 2));
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const int q = tid + i * THREADS;
-            const int row = q >> 3, c = q & 7;
-            const int gk = k0 + c * 8;
-            const unsigned off = (unsigned)(row * ld + gk) * 2u;
-            v[i] = buffer_load16(rsrc, gk < K ? off : OOB_OFFSET);
+        for (int j = 0; j < NI; ++j) {
+            const int q = wid * NI + j;
+            const int row = q * RPI + lane / CPR;
+            const int c = (lane % CPR) ^ sw(row);
+            kc[j] = c * 8;
+            voff[j] = (unsigned)(row * ld + c * 8) * 2u;
         }
     }
-    __device__ __forceinline__ void store(char* lds, int tid) const {
+    __device__ __forceinline__ void load(char* tile, int k0, int wid) const {
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const int q = tid + i * THREADS;
-            const int row = q >> 3, c = q & 7;
-            *reinterpret_cast<uint4*>(lds + row * G_ROWB + ((c ^ swz(row)) << 4)) = v[i];
+        for (int j = 0; j < NI; ++j) {
+            const int q = wid * NI + j;
+            load_to_lds(rsrc, lds_address(tile) + q * 1024, (k0 + kc[j] < K) ? voff[j] + (unsigned)k0 * 2u : OOB_OFFSET);
         }
     }
+    // fragment of the 32 rows starting at rb: lane reads row rb + lane%32, k = 16*kk + 8*(lane/32) .. +7
+    struct Frag {
+        int addr;    // byte address inside the tile for kk = 0
+        __device__ __forceinline__ void init(int rb, int lane) {
+            const int row = rb + (lane & 31);
+            addr = row * ROWB + (((lane >> 5) ^ sw(row)) << 4);
+        }
+        __device__ __forceinline__ bf16x8 read(const char* tile, int kk) const {
+            return *reinterpret_cast<const bf16x8*>(tile + (addr ^ (kk << 5)));
+        }
+    };
 };
 
-// Transposed: operand is [k][n] with n contiguous.  A thread takes a KR(k) x 8(n)
-// block (KR = 8 or 4), transposes it in registers and writes eight K-contiguous
-// pieces of KR elements.  The descriptor starts at the tile's first column and
-// ends after the last valid K row.
-template <int R, int THREADS>
-struct TransTile {
-    static constexpr int NG = R / 8;                  // n-groups per tile
-    static constexpr int KR = (THREADS >= 16 * NG) ? 4 : 8;
-    static_assert(THREADS >= 64 * NG / KR, "not enough threads for the tile");
-    static constexpr int UNITS = NG * (64 / KR);      // threads that carry a block
-    uint4 v[KR];
-    __amdgpu_buffer_rsrc_t rsrc;
-    int ld, n_valid;
-    __device__ __forceinline__ void init(const bf16_t* P, int ld_, int n0, int n_limit, int /*k0*/, int /*unused*/, int K) {
-        ld = ld_;
-        n_valid = n_limit - n0;
-        rsrc = make_rsrc(P + n0, (unsigned)(((size_t)(K - 1) * ld_ + n_valid) * 2));
-    }
-    __device__ __forceinline__ void load(int k0, int /*K*/, int tid) {
-        const int ng = tid % NG, kg = tid / NG;
-        const bool on = tid < UNITS && ng * 8 < n_valid;
+// ---- N-contiguous operand tile: BK k rows x R n --------------------------------------
+// LDS byte of (k, 16-byte unit u) = k*PITCH + (((u + 4*(k&3)) % UPR) << 4): the four k rows
+// that one transposing read touches fall into different banks (64 banks of 4 bytes).
+// One wave instruction fills 1024 bytes = RPI rows: lane l -> row RPI*q + l/UPR, unit l%UPR.
+template <int R, int WAVES, int BK>
+struct NCTile {
+    static constexpr int PITCH = R * 2;                // bytes per k row
+    static constexpr int UPR = R / 8;                  // 16-byte units per row
+    static constexpr int RPI = 1024 / PITCH;           // rows per wave instruction
+    static constexpr int NI = BK / RPI / WAVES;
+    static constexpr int BYTES = BK * PITCH;
+    static_assert(BK % (RPI * WAVES) == 0 && NI >= 1, "rows must divide over the wavefronts");
+    v4i rsrc;
+    unsigned voff[NI];
+    unsigned kstep;          // bytes per k row in memory
+    // P: operand base of this expert ([k][n], n contiguous); rows [0, K) x columns [n0, n_limit) valid
+    __device__ __forceinline__ void init(const bf16_t* P, int ld, int n0, int n_limit, int K, int lane, int wid) {
+        const int n_valid = n_limit - n0;
+        rsrc = make_rsrc(P + n0, (unsigned)(((size_t)(K - 1) * ld + n_valid) * 2));
+        kstep = (unsigned)ld * 2u;
 #pragma unroll
-        for (int j = 0; j < KR; ++j) {
-            const int gk = k0 + kg * KR + j;
-            const unsigned off = (unsigned)(gk * ld + ng * 8) * 2u;
-            v[j] = buffer_load16(rsrc, on ? off : OOB_OFFSET);
+        for (int j = 0; j < NI; ++j) {
+            const int q = wid * NI + j;
+            const int row = q * RPI + lane / UPR;
+            const int u = ((lane % UPR) - 4 * (row & 3) + UPR) % UPR;
+            voff[j] = (u * 8 < n_valid) ? (unsigned)(row * ld + u * 8) * 2u : OOB_OFFSET;
         }
     }
-    __device__ __forceinline__ void store(char* lds, int tid) const {
-        if (tid >= UNITS) return;
-        const int ng = tid % NG, kg = tid / NG;
-        const unsigned* w = reinterpret_cast<const unsigned*>(v);   // w[j*4 + q]
+    __device__ __forceinline__ void load(char* tile, int k0, int wid) const {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int q = i >> 1;
-            const unsigned sel = (i & 1) ? 0x07060302u : 0x05040100u;
-            const int row = ng * 8 + i;
-            if constexpr (KR == 8) {
-                uint4 o;
-                o.x = __builtin_amdgcn_perm(w[1 * 4 + q], w[0 * 4 + q], sel);
-                o.y = __builtin_amdgcn_perm(w[3 * 4 + q], w[2 * 4 + q], sel);
-                o.z = __builtin_amdgcn_perm(w[5 * 4 + q], w[4 * 4 + q], sel);
-                o.w = __builtin_amdgcn_perm(w[7 * 4 + q], w[6 * 4 + q], sel);
-                *reinterpret_cast<uint4*>(lds + row * G_ROWB + ((kg ^ swz(row)) << 4)) = o;
-            } else {
-                uint2 o;
-                o.x = __builtin_amdgcn_perm(w[1 * 4 + q], w[0 * 4 + q], sel);
-                o.y = __builtin_amdgcn_perm(w[3 * 4 + q], w[2 * 4 + q], sel);
-                *reinterpret_cast<uint2*>(lds + row * G_ROWB + (((kg >> 1) ^ swz(row)) << 4) + ((kg & 1) << 3)) = o;
-            }
+        for (int j = 0; j < NI; ++j) {
+            const int q = wid * NI + j;
+            load_to_lds(rsrc, lds_address(tile) + q * 1024, voff[j] + (unsigned)k0 * kstep);
         }
     }
+    // fragment of the 32 columns starting at nb: two transposing reads give the lane
+    // n = nb + lane%32, k = 16*kk + 8*(lane/32) .. +7.  In a 16-lane group lane a points at
+    // row a/4, columns 4*(a%4)..+3; the hardware returns to lane i four k of column i.
+    struct Frag {
+        int addr;
+        __device__ __forceinline__ void init(int nb, int lane) {
+            const int g = lane >> 4, a = lane & 15;
+            const int k_in = 8 * (g >> 1) + (a >> 2);
+            const int n = nb + 16 * (g & 1) + 4 * (a & 3);
+            addr = k_in * PITCH + ((((n >> 3) + 4 * (k_in & 3)) % UPR) << 4) + ((n & 7) << 1);
+        }
+        __device__ __forceinline__ bf16x8 read(const char* tile, int kk) const {
+            const char* p = tile + addr + kk * 16 * PITCH;
+            v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s*)p);
+            v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s*)(p + 4 * PITCH));
+            typedef short v8s __attribute__((ext_vector_type(8)));
+            v8s both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, both);
+        }
+    };
 };
 
-template <int LAY, int R, int T> struct ATile { typedef DirectTile<R, T> type; };
-template <int R, int T> struct ATile<GEMM_TN, R, T> { typedef TransTile<R, T> type; };
-template <int LAY, int R, int T> struct BTile { typedef TransTile<R, T> type; };
-template <int R, int T> struct BTile<GEMM_NT, R, T> { typedef DirectTile<R, T> type; };
+template <int LAY, int R, int W, int BK> struct ATile { typedef KCTile<R, W, BK> type; };
+template <int R, int W, int BK> struct ATile<GEMM_TN, R, W, BK> { typedef NCTile<R, W, BK> type; };
+template <int LAY, int R, int W, int BK> struct BTile { typedef NCTile<R, W, BK> type; };
+template <int R, int W, int BK> struct BTile<GEMM_NT, R, W, BK> { typedef KCTile<R, W, BK> type; };
+
+// s_waitcnt vmcnt(N) only (N <= 63), with a compiler-level memory fence
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+    asm volatile("" ::: "memory");
+}
 
 template <int LAY, int EPI, typename C>
 __global__ __launch_bounds__(C::THREADS) __attribute__((amdgpu_waves_per_eu(C::OCC, C::OCC)))
 void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int BM = C::BM, BN = C::BN, WM = C::WM, WN = C::WN, TM = C::TM, TNN = C::TN;
-    constexpr int STAGE = C::STAGE_BYTES;
+    constexpr int STAGE = C::STAGE_BYTES, BK = C::BK, NS = C::NS;
+    constexpr int A_BYTES = BM * BK * 2;
 
     // ---- workgroup -> (expert, tile) with XCD-aware order ------------------------
     // Hardware deals consecutive workgroup ids round-robin to the 8 XCDs; give each
@@ -188,23 +241,23 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
 
     const bf16_t* A = (const bf16_t*)g.A + (size_t)e * g.a_estride;
     const bf16_t* B = (const bf16_t*)g.B + (size_t)e * g.b_estride;
-    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wid / C::WAVES_N, wn = wid % C::WAVES_N;
 
-    typename ATile<LAY, BM, C::THREADS>::type ta;
-    typename BTile<LAY, BN, C::THREADS>::type tb;
-    const int KT = (Kdim + G_BK - 1) / G_BK;
-
-    ta.init(A, g.lda, m0, Mdim, 0, 0, Kdim);
-    tb.init(B, g.ldb, n0, g.N, 0, 0, Kdim);
-    auto load_tiles = [&](int kt) {
-        ta.load(kt * G_BK, Kdim, tid);
-        tb.load(kt * G_BK, Kdim, tid);
-    };
-    auto store_tiles = [&](int stage) {
-        ta.store(smem + stage * STAGE, tid);
-        tb.store(smem + stage * STAGE + BM * G_ROWB, tid);
-    };
+    typedef typename ATile<LAY, BM, C::WAVES, BK>::type AT;
+    typedef typename BTile<LAY, BN, C::WAVES, BK>::type BT;
+    AT ta;
+    BT tb;
+    ta.init(A, g.lda, m0, Mdim, Kdim, lane, wid);
+    tb.init(B, g.ldb, n0, g.N, Kdim, lane, wid);
+    typename AT::Frag fa[TM];
+    typename BT::Frag fb[TNN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[i].init(wm * WM + i * 32, lane);
+#pragma unroll
+    for (int j = 0; j < TNN; ++j) fb[j].init(wn * WN + j * 32, lane);
+    const int KT = (Kdim + BK - 1) / BK;
 
     floatx16 acc[TM][TNN];
 #pragma unroll
@@ -214,79 +267,43 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // fragment addressing: lane reads tile row (lane & 31), logical chunk 2*kk + (lane >> 5)
-    int a_off[TM], a_sw[TM], b_off[TNN], b_sw[TNN];
+    // Ring of NS stages.  Tiles 0 .. NS-2 are requested up front; in iteration kt
+    // the wave waits until its own part of tile kt has landed (the NS-2 younger
+    // tiles may still be in flight), the barrier makes every wave's part visible
+    // and tells that tile kt-1 has been consumed, whose stage then receives tile
+    // kt+NS-1.  A tile past the end reads as zeros.
+    constexpr int LPW = AT::NI + BT::NI;         // loads per wave per tile
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int row = wm * WM + i * 32 + (lane & 31);
-        a_off[i] = row * G_ROWB;
-        a_sw[i] = swz(row);
+    for (int s = 0; s < NS - 1; ++s) {
+        ta.load(smem + s * STAGE, s * BK, wid);
+        tb.load(smem + s * STAGE + A_BYTES, s * BK, wid);
     }
+    int st_cur = 0, st_free = NS - 1;
+    for (int kt = 0; kt < KT; ++kt) {
+        wait_vmcnt<(NS - 2) * LPW>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        char* cur = smem + st_cur * STAGE;
+        char* nxt = smem + st_free * STAGE;
+        ta.load(nxt, (kt + NS - 1) * BK, wid);
+        tb.load(nxt + A_BYTES, (kt + NS - 1) * BK, wid);
 #pragma unroll
-    for (int j = 0; j < TNN; ++j) {
-        const int row = wn * WN + j * 32 + (lane & 31);
-        b_off[j] = BM * G_ROWB + row * G_ROWB;
-        b_sw[j] = swz(row);
-    }
-    const int khalf = lane >> 5;
-
-    auto compute = [&](const char* base) {
-#pragma unroll
-        for (int kk = 0; kk < G_BK / 16; ++kk) {
+        for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 af[TM], bfr[TNN];
-            const int c = kk * 2 + khalf;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8*>(base + a_off[i] + ((c ^ a_sw[i]) << 4));
+            for (int i = 0; i < TM; ++i) af[i] = fa[i].read(cur, kk);
 #pragma unroll
-            for (int j = 0; j < TNN; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8*>(base + b_off[j] + ((c ^ b_sw[j]) << 4));
+            for (int j = 0; j < TNN; ++j) bfr[j] = fb[j].read(cur + A_BYTES, kk);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TNN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
-    };
-
-    if constexpr (C::STAGES == 2) {
-        load_tiles(0);
-        store_tiles(0);
-        load_tiles(1);                       // tiles past the end read as zeros
-        __syncthreads();
-        for (int kt = 0; kt < KT; ++kt) {
-            const int cur = kt & 1;
-            // One straight-line block per iteration: write tile kt+1 into the other
-            // LDS buffer, start the global reads of tile kt+2, multiply tile kt.
-            store_tiles(cur ^ 1);
-            load_tiles(kt + 2);
-            compute(smem + cur * STAGE);
-            // Issue order for the block: the first fragments, then the matrix
-            // instructions with LDS reads, LDS writes and global reads between them,
-            // so the matrix pipe stays busy while the memory pipes work.
-            constexpr int NMFMA = TM * TNN * (G_BK / 16);
-            constexpr int NDSR = (TM + TNN) * (G_BK / 16);
-            constexpr int FIRST = TM + TNN;
-            __builtin_amdgcn_sched_group_barrier(0x100, FIRST, 0);
-#pragma unroll
-            for (int i = 0; i < NMFMA; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (i < NDSR - FIRST) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                if (i % 2 == 0) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                if (i % 2 == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            }
-            __syncthreads();
-        }
-    } else {
-        load_tiles(0);
-        for (int kt = 0; kt < KT; ++kt) {
-            store_tiles(0);
-            __syncthreads();
-            if (kt + 1 < KT) load_tiles(kt + 1);
-            compute(smem);
-            __syncthreads();
-        }
+        st_free = st_cur;
+        st_cur = (st_cur + 1 == NS) ? 0 : st_cur + 1;
     }
+    wait_vmcnt<0>();                             // nothing of this workgroup is in flight into LDS any more
 
     // ---- epilogue: lane holds row m = (lane & 31), columns 8*g4 + 4*(lane>>5) + 0..3 ----
     // The lane id is passed through an empty asm so that none of the epilogue's
@@ -324,16 +341,16 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
 
 // Tile shape in use.  MOE_GEMM_CFG selects it at build time for experiments.
 #ifndef MOE_GEMM_CFG
-#define MOE_GEMM_CFG 2
+#define MOE_GEMM_CFG 3
 #endif
-#if MOE_GEMM_CFG == 0
-typedef TileCfg<256, 256, 2, 2, 2, 1> Cfg;     // 4 waves of 128x128, double-buffered LDS
-#elif MOE_GEMM_CFG == 1
-typedef TileCfg<128, 256, 2, 2, 1, 2> Cfg;     // 4 waves of 64x128, two workgroups per CU
-#elif MOE_GEMM_CFG == 2
-typedef TileCfg<256, 256, 2, 4, 2, 2> Cfg;     // 8 waves of 128x64, double-buffered LDS
+#if MOE_GEMM_CFG == 2
+typedef TileCfg<256, 256, 32, 5, 2, 4, 2> Cfg;     // 8 waves of 128x64, ring of 5 x 32 k
 #elif MOE_GEMM_CFG == 3
-typedef TileCfg<256, 128, 2, 2, 1, 2> Cfg;     // 4 waves of 128x64, two workgroups per CU
+typedef TileCfg<256, 256, 64, 2, 2, 4, 2> Cfg;     // 8 waves of 128x64, ring of 2 x 64 k
+#elif MOE_GEMM_CFG == 4
+typedef TileCfg<256, 256, 32, 4, 2, 4, 2> Cfg;     // 8 waves of 128x64, ring of 4 x 32 k
+#elif MOE_GEMM_CFG == 5
+typedef TileCfg<256, 256, 32, 3, 2, 4, 2> Cfg;     // 8 waves of 128x64, ring of 3 x 32 k
 #endif
 
 int gemm_bf16_dw_parts(int H) { return ((H + Cfg::BN - 1) / Cfg::BN) * Cfg::WAVES_N; }
@@ -373,6 +390,11 @@ static moe_status launch_lay(GemmEpilogue epi, const GemmArgs& a, hipStream_t s)
 
 moe_status gemm_bf16(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
     if (a.dw_part && a.dw_parts != gemm_bf16_dw_parts(a.N)) return MOE_ERR_SHAPE;
+    // operand rows must be 16-byte aligned in memory
+    if ((a.lda | a.ldb) & 7) return MOE_ERR_UNSUPPORTED;
+    // buffer offsets are 32-bit: an expert's operand must stay below 2 GiB
+    const long long ldmax = a.lda > a.ldb ? a.lda : a.ldb;
+    if (((long long)a.Cp + 8 * 64) * ldmax * 2 >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
     if (lay == GEMM_NN) return launch_lay<GEMM_NN>(epi, a, s);
     if (lay == GEMM_NT) return launch_lay<GEMM_NT>(epi, a, s);
     return launch_lay<GEMM_TN>(epi, a, s);
