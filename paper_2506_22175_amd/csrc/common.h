@@ -66,20 +66,28 @@ template <> struct Vec8<float> {
     }
 };
 
-// exact GeLU (erf form) and its derivative
-__device__ __forceinline__ float gelu_f(float z) {
-    return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
-}
-__device__ __forceinline__ float gelu_grad_f(float z) {
-    float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
-    float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
-    return cdf + z * pdf;
-}
+// GeLU in its erf form, z * Phi(z), and its derivative Phi(z) + z * phi(z).
+// erf is evaluated with the five-term rational approximation of Abramowitz &
+// Stegun 7.1.26 (absolute error below 1.5e-7, far inside the float32 tolerance),
+// which shares its exp(-x^2) with the normal density phi: about twenty
+// instructions for value and derivative together.
 __device__ __forceinline__ void gelu_both_f(float z, float* g, float* dg) {
-    float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
-    float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+    const float x = fabsf(z) * 0.70710678118654752440f;
+    const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
+    const float ex = __expf(-x * x);                       // = exp(-z^2 / 2)
+    float p = fmaf(t, 1.061405429f, -1.453152027f);
+    p = fmaf(t, p, 1.421413741f);
+    p = fmaf(t, p, -0.284496736f);
+    p = fmaf(t, p, 0.254829592f);
+    const float erf_abs = fmaf(-p * t, ex, 1.0f);
+    const float cdf = fmaf(copysignf(0.5f, z), erf_abs, 0.5f);
     *g = z * cdf;
-    *dg = cdf + z * pdf;
+    *dg = fmaf(z * 0.39894228040143267794f, ex, cdf);
+}
+__device__ __forceinline__ float gelu_f(float z) {
+    float g, dg;
+    gelu_both_f(z, &g, &dg);
+    return g;
 }
 
 struct Dims {
