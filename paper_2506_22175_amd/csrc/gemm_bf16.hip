@@ -308,37 +308,57 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
         st_cur = (st_cur + 1 == NS) ? 0 : st_cur + 1;
     }
     wait_vmcnt<0>();                             // nothing of this workgroup is in flight into LDS any more
+    __builtin_amdgcn_s_barrier();                // and every wave is done reading the ring
+    asm volatile("" ::: "memory");
 
-    // ---- epilogue: lane holds row m = (lane & 31), columns 8*g4 + 4*(lane>>5) + 0..3 ----
-    // The lane id is passed through an empty asm so that none of the epilogue's
-    // address arithmetic is hoisted above the main loop, where registers are scarce.
-    int elane = lane;
-    asm volatile("" : "+v"(elane));
-    const int erow = elane & 31, ehalf = elane >> 5;
+    // ---- epilogue -----------------------------------------------------------------------
+    // An MFMA accumulator holds one row per lane (row = lane & 31, four consecutive
+    // columns per register group), which would make every global access a 8- or 16-byte
+    // piece of 32 different rows.  Each wave therefore passes its 32 x WN blocks through a
+    // private LDS region (float, 16-byte chunks XOR-swizzled by row) and picks them up
+    // with eight consecutive columns per lane, so that eight lanes cover a whole line of
+    // a row: all global reads and writes of the epilogue are 16 or 32 bytes per lane,
+    // row-contiguous.
+    constexpr int CPRW = WN / 8;                 // 8-column pieces per row of the wave's block
+    constexpr int NPIECE = 32 * CPRW / 64;       // pieces per lane
+    float* stage = reinterpret_cast<float*>(smem + wid * (32 * WN * 4));
+    static_assert(C::WAVES * 32 * WN * 4 <= C::LDS_BYTES, "staging does not fit");
     EpiCtx<bf16_t> c;
     c.ldc = g.ldc; c.ldz = g.ldz;
     c.C = (bf16_t*)g.C + (size_t)e * g.c_estride;
     c.Cf = (float*)g.C + (size_t)e * g.c_estride;
     c.Z = g.Z ? (bf16_t*)g.Z + (size_t)e * g.Cp * g.ldz : nullptr;
     c.w = g.slot_w ? g.slot_w + (size_t)e * g.Cp : nullptr;
+    const int erow = lane & 31, ehalf = lane >> 5;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm * WM + i * 32 + erow;
-        float dot = 0.0f;
 #pragma unroll
         for (int j = 0; j < TNN; ++j) {
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                const int n = n0 + wn * WN + j * 32 + g4 * 8 + ehalf * 4;
-                float v[4] = {acc[i][j][g4 * 4 + 0], acc[i][j][g4 * 4 + 1], acc[i][j][g4 * 4 + 2], acc[i][j][g4 * 4 + 3]};
-                if (m < Mdim && n < g.N) dot += epilogue4<bf16_t, EPI>(c, m, n, v);
+                const int cch = (j * 32 + g4 * 8 + ehalf * 4) >> 2;
+                float4 v = make_float4(acc[i][j][g4 * 4 + 0], acc[i][j][g4 * 4 + 1], acc[i][j][g4 * 4 + 2], acc[i][j][g4 * 4 + 3]);
+                *reinterpret_cast<float4*>(stage + erow * WN + ((cch ^ (erow & 15)) << 2)) = v;
             }
-            __builtin_amdgcn_sched_barrier(0);   // keep one 32x32 tile's loads and stores together
         }
-        if (EPI == EPI_DGELU && g.dw_part) {
-            dot += __shfl_xor(dot, 32, 64);
-            if (elane < 32 && m < Mdim)
-                g.dw_part[((size_t)e * g.Cp + m) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
+#pragma unroll
+        for (int t = 0; t < NPIECE; ++t) {
+            const int idx = lane + 64 * t;
+            const int row = idx / CPRW, c8 = idx % CPRW;
+            const float4 lo = *reinterpret_cast<const float4*>(stage + row * WN + (((2 * c8) ^ (row & 15)) << 2));
+            const float4 hi = *reinterpret_cast<const float4*>(stage + row * WN + (((2 * c8 + 1) ^ (row & 15)) << 2));
+            const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            const int m = m0 + wm * WM + i * 32 + row;
+            const int n = n0 + wn * WN + c8 * 8;
+            float dot = 0.0f;
+            if (m < Mdim && n < g.N) dot = epilogue8<bf16_t, EPI>(c, m, n, v);
+            if (EPI == EPI_DGELU && g.dw_part) {
+                // the CPRW lanes of a row are neighbours
+#pragma unroll
+                for (int off = CPRW / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
+                if (c8 == 0 && m < Mdim)
+                    g.dw_part[((size_t)e * g.Cp + m) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
+            }
         }
     }
 }
