@@ -112,50 +112,59 @@ __global__ __launch_bounds__(PERM_THREADS) void dispatch_bwd_kernel(
         for (int e = 0; e < EC; ++e) wg[i][e] = e < E ? Elem<T>::ld(Wg + (size_t)(c + i) * E + e) : 0.0f;
     const int tl0 = blockIdx.y * DXB_TOK;
     const int tl1 = min(tl0 + DXB_TOK, t_count);
-    for (int tl = tl0; tl < tl1; ++tl) {
-        const int t = t_begin + tl;
-        float acc[8];
+    // four tokens per round so that their row reads are in flight together
+    for (int tb = tl0; tb < tl1; tb += 4) {
+        float acc[4][8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
-        for (int j = 0; j < k; ++j) {
-            int s = slot[(size_t)t * k + j];
-            if (s < 0) continue;
-            float r[8];
-            Vec8<T>::load(dDI + (size_t)s * M + c, r);
+        for (int u = 0; u < 4; ++u) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] += r[i];
+            for (int i = 0; i < 8; ++i) acc[u][i] = 0.0f;
+            const int tl = tb + u;
+            if (tl >= tl1) continue;
+            const int t = t_begin + tl;
+            for (int j = 0; j < k; ++j) {
+                int s = slot[(size_t)t * k + j];
+                if (s < 0) continue;
+                float r[8];
+                Vec8<T>::load(dDI + (size_t)s * M + c, r);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[u][i] += r[i];
+            }
         }
-        for (int e0 = 0; e0 < E; e0 += EC) {
 #pragma unroll
-            for (int e = 0; e < EC; ++e) {
-                if (e0 + e < E) {
-                    float g = dL[(size_t)t * E + e0 + e];
-                    if (E <= EC) {
+        for (int u = 0; u < 4; ++u) {
+            const int tl = tb + u;
+            if (tl >= tl1) continue;
+            const int t = t_begin + tl;
+            for (int e0 = 0; e0 < E; e0 += EC) {
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) acc[i] = fmaf(g, wg[i][e], acc[i]);
-                    } else {
+                for (int e = 0; e < EC; ++e) {
+                    if (e0 + e < E) {
+                        float g = dL[(size_t)t * E + e0 + e];
+                        if (E <= EC) {
 #pragma unroll
-                        for (int i = 0; i < 8; ++i)
-                            acc[i] = fmaf(g, Elem<T>::ld(Wg + (size_t)(c + i) * E + e0 + e), acc[i]);
+                            for (int i = 0; i < 8; ++i) acc[u][i] = fmaf(g, wg[i][e], acc[u][i]);
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i)
+                                acc[u][i] = fmaf(g, Elem<T>::ld(Wg + (size_t)(c + i) * E + e0 + e), acc[u][i]);
+                        }
                     }
                 }
             }
+            Vec8<T>::store(dx + (size_t)t * M + c, acc[u]);
         }
-        Vec8<T>::store(dx + (size_t)t * M + c, acc);
     }
 }
 
 // ---- gate backward ------------------------------------------------------------
 
 // dL[t,e] = p[t,e] * (dp[t,e] - sum_e' dp[t,e'] p[t,e']) with dp nonzero only at the
-// chosen experts.  One thread per token.
-__global__ __launch_bounds__(256) void gate_dl_kernel(
+// chosen experts; one thread per token.
+__device__ __forceinline__ void gate_dl_token(
     const float* __restrict__ logits, const int* __restrict__ topk_idx, const int* __restrict__ slot,
     const float* __restrict__ dw, const float* __restrict__ dw_part, int parts,
-    float* __restrict__ dL, int t_begin, int t_count, int E, int k) {
-    const int tl = blockIdx.x * 256 + threadIdx.x;
-    if (tl >= t_count) return;
-    const int t = t_begin + tl;
+    float* __restrict__ dL, float* sdl, int t, int E, int k) {
     const float* lg = logits + (size_t)t * E;
     float mx = -INFINITY;
     for (int e = 0; e < E; ++e) mx = fmaxf(mx, lg[e]);
@@ -182,49 +191,64 @@ __global__ __launch_bounds__(256) void gate_dl_kernel(
         float p = expf(lg[e] - mx) * inv;
         float dp = 0.0f;
         for (int j = 0; j < k; ++j) if (ids[j] == e) dp = g[j];
-        dL[(size_t)t * E + e] = p * (dp - inner);
+        const float v = p * (dp - inner);
+        dL[(size_t)t * E + e] = v;
+        sdl[e] = v;
     }
 }
 
-// part[b][d][e] = sum over the block's tokens of x[t,d] * dL[t,e]
-constexpr int DWG_TOK = 256;
+// One workgroup takes DWG_TOK tokens: first dL of those tokens (to global memory for the
+// dispatch-backward kernel, and to LDS), then part[b][d][e] = sum over the tokens of
+// x[t,d] * dL[t,e], each thread owning eight columns d.
+constexpr int DWG_TOK = 64;
+constexpr int DWG_EMAX = 64;
 template <typename T>
-__global__ __launch_bounds__(PERM_THREADS) void gate_dwg_partial_kernel(
-    const T* __restrict__ x, const float* __restrict__ dL, float* __restrict__ part,
-    int t_begin, int t_count, int M, int E) {
-    __shared__ float sdl[DWG_TOK][16];
-    const int c = (blockIdx.x * PERM_THREADS + threadIdx.x) * 8;
+__global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
+    const T* __restrict__ x, const float* __restrict__ logits, const int* __restrict__ topk_idx,
+    const int* __restrict__ slot, const float* __restrict__ dw, const float* __restrict__ dw_part, int parts,
+    float* __restrict__ dL, float* __restrict__ part, int t_begin, int t_count, int M, int E, int k) {
+    __shared__ float sdl[DWG_TOK][DWG_EMAX + 1];
     const int tl0 = blockIdx.y * DWG_TOK;
     const int nt = min(DWG_TOK, t_count - tl0);
-    const int e0 = blockIdx.z * 16;
-    const int ne = min(16, E - e0);
-    for (int q = threadIdx.x; q < nt * 16; q += PERM_THREADS) {
-        int i = q / 16, e = q % 16;
-        sdl[i][e] = e < ne ? dL[(size_t)(t_begin + tl0 + i) * E + e0 + e] : 0.0f;
-    }
+    if ((int)threadIdx.x < nt)
+        gate_dl_token(logits, topk_idx, slot, dw, dw_part, parts, dL, sdl[threadIdx.x], t_begin + tl0 + threadIdx.x, E, k);
     __syncthreads();
-    if (c >= M) return;
-    float acc[8][16];
+    for (int c = threadIdx.x * 8; c < M; c += PERM_THREADS * 8) {
+        for (int e0 = 0; e0 < E; e0 += 16) {
+            const int ne = min(16, E - e0);
+            float acc[8][16];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
-    for (int i = 0; i < nt; ++i) {
-        float xv[8];
-        Vec8<T>::load(x + (size_t)(t_begin + tl0 + i) * M + c, xv);
+                for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
+            for (int i0 = 0; i0 < nt; i0 += 4) {
+                float xv[4][8];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            float g = sdl[i][e];
+                for (int u = 0; u < 4; ++u) {
+                    if (i0 + u < nt) Vec8<T>::load(x + (size_t)(t_begin + tl0 + i0 + u) * M + c, xv[u]);
+                    else {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q][e] = fmaf(xv[q], g, acc[q][e]);
+                        for (int q = 0; q < 8; ++q) xv[u][q] = 0.0f;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const float gd = (e < ne && i0 + u < nt) ? sdl[i0 + u][e0 + e] : 0.0f;
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) acc[q][e] = fmaf(xv[u][q], gd, acc[q][e]);
+                    }
+                }
+            }
+            float* out = part + ((size_t)blockIdx.y * M + c) * E + e0;
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    if (e < ne) out[(size_t)q * E + e] = acc[q][e];
         }
     }
-    float* out = part + ((size_t)blockIdx.y * M + c) * E + e0;
-#pragma unroll
-    for (int q = 0; q < 8; ++q)
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-            if (e < ne) out[(size_t)q * E + e] = acc[q][e];
 }
 
 __global__ __launch_bounds__(256) void gate_dwg_reduce_kernel(
@@ -273,18 +297,14 @@ static moe_status gate_bwd_t(const Dims& d, int part, const void* x, const float
                              const int* slot, const float* dw, const float* dw_part, int parts,
                              float* dL, float* dWg, void* scratch, hipStream_t s) {
     ProfScope ps(PK_GATE_BWD, s);
-    hipLaunchKernelGGL(gate_dl_kernel, dim3((d.Tp + 255) / 256), dim3(256), 0, s, logits, idx, slot, dw,
-                       dw_part, parts, dL, part * d.Tp, d.Tp, d.E, d.k);
-    MOE_CHECK_LAUNCH();
     const int nblk = (d.Tp + DWG_TOK - 1) / DWG_TOK;
-    dim3 grid((d.M / 8 + PERM_THREADS - 1) / PERM_THREADS, nblk, (d.E + 15) / 16);
-    hipLaunchKernelGGL((gate_dwg_partial_kernel<T>), grid, dim3(PERM_THREADS), 0, s, (const T*)x, dL,
-                       (float*)scratch, part * d.Tp, d.Tp, d.M, d.E);
+    hipLaunchKernelGGL((gate_bwd_kernel<T>), dim3(1, nblk), dim3(PERM_THREADS), 0, s, (const T*)x, logits, idx,
+                       slot, dw, dw_part, parts, dL, (float*)scratch, part * d.Tp, d.Tp, d.M, d.E, d.k);
     MOE_CHECK_LAUNCH();
     const int ME = d.M * d.E;
     hipLaunchKernelGGL(gate_dwg_reduce_kernel, dim3((ME + 255) / 256), dim3(256), 0, s,
                        (const float*)scratch, dWg, nblk, ME);
-    count_launch(LC_OTHER, 3);
+    count_launch(LC_OTHER, 2);
     MOE_CHECK_LAUNCH();
     return MOE_OK;
 }

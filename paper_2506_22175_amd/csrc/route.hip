@@ -166,16 +166,23 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
 template <typename T, int EP, int TB>
 static moe_status launch_route(const Dims& d, const void* x, const void* Wg, const float* bias,
                                float* logits, int* idx, float* w, hipStream_t s) {
-    // gate-weight rows per LDS pass: 64 KB of floats, at least one 512-element span
-    int MC = (16384 / EP) / 512 * 512;
-    if (MC < 512) MC = 512;
-    if (MC > ((d.M + 511) / 512) * 512) MC = ((d.M + 511) / 512) * 512;
+    // Gate-weight rows held in LDS at a time.  If the whole matrix fits in 128 KB of
+    // floats it is loaded once per workgroup, which then walks over many token groups;
+    // otherwise it is streamed through LDS in 64 KB pieces for every token group.
+    const int Mpad = ((d.M + 511) / 512) * 512;
+    int MC = (32768 / EP) / 512 * 512;
+    if (Mpad <= MC) MC = Mpad;
+    else {
+        MC = (16384 / EP) / 512 * 512;
+        if (MC < 512) MC = 512;
+    }
     size_t lds = ((size_t)MC * EP + (size_t)ROUTE_WAVES * TB * EP) * sizeof(float);
     auto kern = route_kernel<T, EP, TB>;
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds));
     int ngroups = (d.T + ROUTE_WAVES * TB - 1) / (ROUTE_WAVES * TB);
-    int grid = ngroups < 1024 ? ngroups : 1024;
+    const int cap = lds > 80 * 1024 ? 256 : 512;      // one or two workgroups per CU fit
+    int grid = ngroups < cap ? ngroups : cap;
     ProfScope ps(PK_ROUTE, s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(ROUTE_THREADS), lds, s,
                        (const T*)x, (const T*)Wg, bias, logits, idx, w, d.T, d.M, d.E, d.k, MC);
