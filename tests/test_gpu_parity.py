@@ -217,3 +217,94 @@ def test_skewed_workload_sampled(oracle, runner):
 def test_large_workload_sampled_in_bench_configuration(oracle, runner):
     """The shape and launch configuration bench.py times."""
     _sampled_check(oracle, runner, synth.WORKLOADS["large"], 2, 2, n_tokens=48)
+
+
+# ---------------------------------------------------------------------------------
+# schedule: op counts of Table II, and the entry points one by one
+# ---------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode,gemm_bwd,perm_bwd", [(0, 4, 2), (1, 4, 3), (2, 5, 3)])
+def test_launch_counts_match_table_two(runner, mode, gemm_bwd, perm_bwd):
+    """Per partition: forward 2 GEMMs and 2 permutations; backward 4 GEMMs and 2
+    permutations, 3 permutations when T_DI is dispatched again, 5 GEMMs when T_M is
+    recomputed (the paper's Q vectors [2,2,0] and [4,2,0] / [5,3,0])."""
+    from paper_2506_22175_amd import binding as B
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=0)
+    n = 4
+    st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, n, s.dtype, mode)
+    st.upload(d)
+    st.zero_grads()
+    B.moe_launch_counts(reset=True)
+    st.forward()
+    torch.cuda.synchronize()
+    g, p, _ = B.moe_launch_counts(reset=True)
+    assert (g, p) == (2 * n, 2 * n)
+    st.backward()
+    torch.cuda.synchronize()
+    g, p, _ = B.moe_launch_counts(reset=True)
+    assert (g, p) == (gemm_bwd * n, perm_bwd * n)
+
+
+def test_entry_points_one_by_one_equal_the_layer_step(oracle, runner):
+    """Route, slots, dispatch, FFN forward, combine, and the backward pieces called
+    through the C ABI one at a time give what moe_layer_step gives."""
+    from paper_2506_22175_amd import binding as B
+    s = synth.custom_shape(640, 256, 384, 6, 2, 0.8, dtype="bf16", w_std=0.05)
+    d = synth.make_inputs(s, seed=5)
+    n = 2
+    ref = runner.run_layer_step(s, d, n, 2)
+    orc = _oracle(oracle, s, d, n)
+    st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, n, s.dtype, 2)
+    st.upload(d)
+    st.poison()
+    st.zero_grads()
+    cfg, i = st.cfg, st.inputs
+    dev, bf = "cuda:0", torch.bfloat16
+    Rp = st.C_p * s.E
+    parts = B.moe_dw_parts(cfg)
+    slot_w = torch.full((n * Rp,), float("nan"), device=dev)
+    sscr = torch.empty(B.moe_slot_scratch_bytes(cfg), dtype=torch.uint8, device=dev)
+    gscr = torch.empty(B.moe_gate_scratch_bytes(cfg), dtype=torch.uint8, device=dev)
+    B.moe_route(cfg, i["x"], i["Wg"], None, st.logits, st.topk_idx, st.topk_w)
+    B.moe_assign_slots(cfg, st.topk_idx, st.topk_w, st.slot, st.counts, slot_w, sscr)
+    assert np.array_equal(st.slot.cpu().numpy(), orc["slot"])
+    dL = torch.full((s.T, s.E), float("nan"), device=dev)
+    for p in range(n):
+        nan = float("nan")
+        DI = torch.full((Rp, s.M), nan, dtype=bf, device=dev)
+        A = torch.full((Rp, s.H), nan, dtype=bf, device=dev)
+        DO = torch.full((Rp, s.M), nan, dtype=bf, device=dev)
+        B.moe_dispatch(cfg, p, i["x"], st.slot, DI)
+        B.moe_expert_ffn_fwd(cfg, p, DI, st.counts, i["W1"], i["W2"], None, A, DO)
+        B.moe_combine(cfg, p, DO, st.slot, st.topk_w, st.y)
+        dDO = torch.full((Rp, s.M), nan, dtype=bf, device=dev)
+        Z = torch.full((Rp, s.H), nan, dtype=bf, device=dev)
+        dZ = torch.full((Rp, s.H), nan, dtype=bf, device=dev)
+        dDI = torch.full((Rp, s.M), nan, dtype=bf, device=dev)
+        dwp = torch.full((Rp, parts), nan, device=dev)
+        B.moe_dispatch(cfg, p, i["dy"], st.slot, dDO)
+        B.moe_expert_ffn_bwd(cfg, p, 1, DI, Z, dDO, st.counts, slot_w, i["W1"], i["W2"], dZ, dDI, st.dW1, st.dW2, dwp)
+        B.moe_gate_bwd(cfg, p, i["x"], st.logits, st.topk_idx, st.slot, None, dwp, dL, st.dWg, gscr)
+        B.moe_dispatch_bwd(cfg, p, dDI, st.slot, dL, i["Wg"], st.dx)
+    got = st.results()
+    for k_ in ("y", "dx", "dWg", "dW1", "dW2"):
+        assert np.array_equal(got[k_], ref[k_]), k_
+    _check_values(got, orc, TOL["bf16"])
+
+
+def test_kernel_timing_hooks_see_every_gemm(runner):
+    from paper_2506_22175_amd import binding as B
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=0)
+    st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, 2, s.dtype, 2)
+    st.upload(d)
+    st.zero_grads()
+    B.moe_profile_enable(True)
+    st.step()
+    torch.cuda.synchronize()
+    B.moe_profile_enable(False)
+    prof = B.moe_profile_read()
+    assert prof["gemm_fwd1_gelu"][0] == 2 and prof["gemm_nn_store"][0] == 4 and prof["gemm_wgrad"][0] == 4
+    assert prof["gemm_dgelu"][0] == 2 and prof["gemm_dgrad"][0] == 2 and prof["dispatch"][0] == 6
+    assert all(ms > 0 for cnt, ms in prof.values() if cnt)
