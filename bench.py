@@ -46,6 +46,19 @@ def cpu_baseline(shape, inp, budget_tokens):
             "sample": f"first {Ts} of {shape.T} tokens, full weights, one partition, float64 numpy, {dt:.1f} s"}
 
 
+def recorded_traffic(workload, n, reuse):
+    """HBM-side bytes per GEMM launch recorded from rocprofv3 --pmc runs (FETCH_SIZE +
+    WRITE_SIZE, calibrated on the dispatch kernel); None if no record for this setup."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}_n{n}_reuse{reuse}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("gemm_traffic_bytes_per_launch"):
+                return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,7 +132,8 @@ def main():
                             "tflops": 2.0 * R * M * H * gemms_per_row[kd] * args.steps / (ms * 1e-3) / 1e12}
     roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (grouped expert GEMM, all layouts)",
                 "achieved": achieved_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                "frac": achieved_tflops / PEAK_BF16_TFLOPS,
+                "traffic": recorded_traffic(args.workload, args.n, args.reuse),
                 "launches": g_launch, "avg_launch_us": 1e3 * g_ms / max(g_launch, 1),
                 "flop_per_launch": g_flop_per_step * args.steps / max(g_launch, 1), "per_use": per_kind}
 
