@@ -59,6 +59,135 @@ def recorded_traffic(workload, n, reuse):
     return None
 
 
+def measure(args, workload, n, reuse, steps, warmup, brief=False):
+    """Time `steps` whole layer steps of one workload; returns the result dict and the inputs."""
+    import numpy as np
+    import torch
+    from paper_2506_22175_amd import binding as B
+    from paper_2506_22175_amd import runner, synth
+
+    shape = synth.WORKLOADS[workload]
+    inp = synth.make_inputs(shape, seed=0)
+    st = runner.LayerState(shape.T, shape.M, shape.H, shape.E, shape.k, shape.capacity_factor, n,
+                           shape.dtype, reuse, second_stream=not args.single_stream)
+    st.upload(inp)
+    st.zero_grads()
+    torch.cuda.reset_peak_memory_stats()
+
+    for _ in range(warmup):
+        st.step()
+    torch.cuda.synchronize()
+
+    graph = st.capture() if args.graph else None
+    run_step = graph.replay if graph is not None else st.step
+    if graph is not None:
+        for _ in range(2):
+            run_step()
+    B.moe_profile_enable(graph is None)
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(st.s0)
+    for _ in range(steps):
+        run_step()
+    ev1.record(st.s0)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    B.moe_profile_enable(False)
+    prof = B.moe_profile_read()
+    kernel_timing = "HIP events on each kernel's own stream, inside the timed region"
+    if graph is not None:
+        # a graph replay cannot carry the timing events: time the kernels in an eager pass after it
+        B.moe_profile_enable(True)
+        for _ in range(steps):
+            st.step()
+        torch.cuda.synchronize()
+        B.moe_profile_enable(False)
+        prof = B.moe_profile_read()
+        kernel_timing = "HIP events in an eager pass of the same number of steps after the timed graph replays"
+    ev_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall_ms / steps
+    peak_alloc = torch.cuda.max_memory_allocated()
+
+    counts = st.counts.cpu().numpy()
+    slot = st.slot.cpu().numpy()
+    R = int(counts.sum())                       # kept rows over all partitions
+    drop_rate = float((slot < 0).mean())
+    T, M, H, k = shape.T, shape.M, shape.H, shape.k
+    es = 2 if shape.dtype == "bf16" else 4
+    gemms_per_row = {"gemm_fwd1_gelu": 1, "gemm_nn_store": 1 + (1 if reuse == 2 else 0), "gemm_dgelu": 1,
+                     "gemm_dgrad": 1, "gemm_wgrad": 2}
+    flop_model = 12.0 * R * M * H
+    flop_exec = flop_model + (2.0 * R * M * H if reuse == 2 else 0.0)
+
+    # dominant kernel: the grouped GEMM (all five uses of the one MFMA kernel)
+    g_launch = sum(prof[kd][0] for kd in GEMM_KINDS)
+    g_ms = sum(prof[kd][1] for kd in GEMM_KINDS)
+    g_flop_per_step = sum(2.0 * R * M * H * gemms_per_row[kd] for kd in GEMM_KINDS)
+    achieved_tflops = g_flop_per_step * steps / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
+    per_kind = {}
+    for kd in GEMM_KINDS:
+        l, ms = prof[kd]
+        if l:
+            per_kind[kd] = {"launches": l, "avg_us": 1e3 * ms / l,
+                            "tflops": 2.0 * R * M * H * gemms_per_row[kd] * steps / (ms * 1e-3) / 1e12}
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (grouped expert GEMM, all layouts)",
+                "achieved": achieved_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved_tflops / PEAK_BF16_TFLOPS,
+                "traffic": recorded_traffic(workload, n, reuse),
+                "launches": g_launch, "avg_launch_us": 1e3 * g_ms / max(g_launch, 1),
+                "flop_per_launch": g_flop_per_step * steps / max(g_launch, 1), "per_use": per_kind,
+                "kernel_timing": kernel_timing}
+
+    # HBM-bound permutations: algorithmic bytes = rows read + rows written
+    n_disp_per_step = 1 + (2 if reuse else 1)          # x forward; dy (+ x again) backward
+    bytes_dispatch = 2.0 * R * M * es                       # per dispatch of all partitions
+    bytes_combine = (R + T) * M * es + T * k * 8.0
+    bytes_dbwd = (R + T) * M * es + T * shape.E * 4.0
+    hbm = {}
+    for name, nbytes, per_step in (("dispatch", bytes_dispatch, n_disp_per_step), ("combine", bytes_combine, 1),
+                                   ("dispatch_bwd", bytes_dbwd, 1)):
+        l, ms = prof[name]
+        if l and ms > 0:
+            gbs = nbytes * per_step * steps / (ms * 1e-3) / 1e9
+            hbm[name] = {"launches": l, "avg_us": 1e3 * ms / l, "GB/s": gbs, "frac": gbs / PEAK_HBM_GBS}
+
+    mem = {}
+    for mode in (0, 1, 2):
+        cfg = B.make_config(T, M, H, shape.E, k, shape.capacity_factor, n,
+                            B.MOE_BF16 if shape.dtype == "bf16" else B.MOE_F32, mode)
+        total, saved, temp, routing = B.moe_workspace_bytes(cfg)
+        mem[f"mode{mode}"] = {"workspace": total, "saved_activations": saved, "temporaries": temp, "routing": routing}
+    mem["max_memory_allocated_this_run"] = int(peak_alloc)
+
+    out = {
+        "metric": "MoE layer fwd+bwd tokens/sec", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_events": ev_ms / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{shape.name}: T={T} M={M} H={H} E={shape.E} k={k} cf={shape.capacity_factor}",
+                   "n_partitions": n, "reuse_mode": reuse, "streams": 1 if args.single_stream else 2,
+                   "hip_graph": bool(args.graph),
+                   "kept_rows": R, "drop_rate": drop_rate},
+        "tflops_model": flop_model / (ms_per_step * 1e-3) / 1e12,
+        "tflops_executed": flop_exec / (ms_per_step * 1e-3) / 1e12,
+        "roofline": roofline, "hbm_kernels": hbm, "memory_bytes": mem,
+        "other_kernels_ms_per_step": {kd: prof[kd][1] / steps for kd in ("route", "slots", "gate_bwd")},
+        "paper_context": "MPipeMoE reports up to 2.8x speedup and up to 47% less memory than FasterMoE on 64 A100 "
+                         "GPUs (8 DGX A100); ratios on other hardware, not a target for this number",
+    }
+    if brief:
+        out = {"workload": out["config"]["workload"], "n_partitions": n, "reuse_mode": reuse, "tokens_per_s": out["value"],
+               "ms_per_step": out["ms_per_step"], "tflops_executed": out["tflops_executed"],
+               "gemm_tflops": roofline["achieved"], "gemm_frac_of_peak": roofline["frac"],
+               "drop_rate": drop_rate, "workspace_bytes": mem[f"mode{reuse}"]["workspace"]}
+    del st
+    torch.cuda.empty_cache()
+    return out, shape, inp
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,113 +199,23 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--single-stream", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=2048)
+    ap.add_argument("--graph", action="store_true", help="replay a captured HIP graph of the step (no per-kernel timing)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the short runs of the other workloads")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
-    import numpy as np
-    import torch
-    from paper_2506_22175_amd import binding as B
-    from paper_2506_22175_amd import runner, synth
-
-    shape = synth.WORKLOADS[args.workload]
-    inp = synth.make_inputs(shape, seed=0)
-    st = runner.LayerState(shape.T, shape.M, shape.H, shape.E, shape.k, shape.capacity_factor, args.n,
-                           shape.dtype, args.reuse, second_stream=not args.single_stream)
-    st.upload(inp)
-    st.zero_grads()
-    torch.cuda.reset_peak_memory_stats()
-
-    for _ in range(args.warmup):
-        st.step()
-    torch.cuda.synchronize()
-
-    B.moe_profile_enable(True)
-    ev0 = torch.cuda.Event(enable_timing=True)
-    ev1 = torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record(st.s0)
-    for _ in range(args.steps):
-        st.step()
-    ev1.record(st.s0)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    B.moe_profile_enable(False)
-    prof = B.moe_profile_read()
-    ev_ms = ev0.elapsed_time(ev1)
-    ms_per_step = wall_ms / args.steps
-    peak_alloc = torch.cuda.max_memory_allocated()
-
-    counts = st.counts.cpu().numpy()
-    slot = st.slot.cpu().numpy()
-    R = int(counts.sum())                       # kept rows over all partitions
-    drop_rate = float((slot < 0).mean())
-    T, M, H, k = shape.T, shape.M, shape.H, shape.k
-    es = 2 if shape.dtype == "bf16" else 4
-    gemms_per_row = {"gemm_fwd1_gelu": 1, "gemm_nn_store": 1 + (1 if args.reuse == 2 else 0), "gemm_dgelu": 1,
-                     "gemm_dgrad": 1, "gemm_wgrad": 2}
-    flop_model = 12.0 * R * M * H
-    flop_exec = flop_model + (2.0 * R * M * H if args.reuse == 2 else 0.0)
-
-    # dominant kernel: the grouped GEMM (all five uses of the one MFMA kernel)
-    g_launch = sum(prof[kd][0] for kd in GEMM_KINDS)
-    g_ms = sum(prof[kd][1] for kd in GEMM_KINDS)
-    g_flop_per_step = sum(2.0 * R * M * H * gemms_per_row[kd] for kd in GEMM_KINDS)
-    achieved_tflops = g_flop_per_step * args.steps / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
-    per_kind = {}
-    for kd in GEMM_KINDS:
-        l, ms = prof[kd]
-        if l:
-            per_kind[kd] = {"launches": l, "avg_us": 1e3 * ms / l,
-                            "tflops": 2.0 * R * M * H * gemms_per_row[kd] * args.steps / (ms * 1e-3) / 1e12}
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (grouped expert GEMM, all layouts)",
-                "achieved": achieved_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved_tflops / PEAK_BF16_TFLOPS,
-                "traffic": recorded_traffic(args.workload, args.n, args.reuse),
-                "launches": g_launch, "avg_launch_us": 1e3 * g_ms / max(g_launch, 1),
-                "flop_per_launch": g_flop_per_step * args.steps / max(g_launch, 1), "per_use": per_kind}
-
-    # HBM-bound permutations: algorithmic bytes = rows read + rows written
-    n_disp_per_step = 1 + (2 if args.reuse else 1)          # x forward; dy (+ x again) backward
-    bytes_dispatch = 2.0 * R * M * es                       # per dispatch of all partitions
-    bytes_combine = (R + T) * M * es + T * k * 8.0
-    bytes_dbwd = (R + T) * M * es + T * shape.E * 4.0
-    hbm = {}
-    for name, nbytes, per_step in (("dispatch", bytes_dispatch, n_disp_per_step), ("combine", bytes_combine, 1),
-                                   ("dispatch_bwd", bytes_dbwd, 1)):
-        l, ms = prof[name]
-        if l and ms > 0:
-            gbs = nbytes * per_step * args.steps / (ms * 1e-3) / 1e9
-            hbm[name] = {"launches": l, "avg_us": 1e3 * ms / l, "GB/s": gbs, "frac": gbs / PEAK_HBM_GBS}
-
-    mem = {}
-    for mode in (0, 1, 2):
-        cfg = B.make_config(T, M, H, shape.E, k, shape.capacity_factor, args.n,
-                            B.MOE_BF16 if shape.dtype == "bf16" else B.MOE_F32, mode)
-        total, saved, temp, routing = B.moe_workspace_bytes(cfg)
-        mem[f"mode{mode}"] = {"workspace": total, "saved_activations": saved, "temporaries": temp, "routing": routing}
-    mem["max_memory_allocated_this_run"] = int(peak_alloc)
-
-    out = {
-        "metric": "MoE layer fwd+bwd tokens/sec", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "ms_per_step_events": ev_ms / args.steps,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype,
-        "data": "synthetic",
-        "config": {"workload": f"{shape.name}: T={T} M={M} H={H} E={shape.E} k={k} cf={shape.capacity_factor}",
-                   "n_partitions": args.n, "reuse_mode": args.reuse, "streams": 1 if args.single_stream else 2,
-                   "kept_rows": R, "drop_rate": drop_rate},
-        "tflops_model": flop_model / (ms_per_step * 1e-3) / 1e12,
-        "tflops_executed": flop_exec / (ms_per_step * 1e-3) / 1e12,
-        "roofline": roofline, "hbm_kernels": hbm, "memory_bytes": mem,
-        "other_kernels_ms_per_step": {kd: prof[kd][1] / args.steps for kd in ("route", "slots", "gate_bwd")},
-        "paper_context": "MPipeMoE reports up to 2.8x speedup and up to 47% less memory than FasterMoE on 64 A100 "
-                         "GPUs (8 DGX A100); ratios on other hardware, not a target for this number",
-    }
+    out, shape, inp = measure(args, args.workload, args.n, args.reuse, args.steps, args.warmup)
+    if not args.no_sweep:
+        # the other workloads of the set, a few steps each, for the record
+        others = []
+        for wl, n in (("small", 1), ("gpt", 1), ("gpt", 4), ("skewed", 4), ("large", 4), ("large", 8)):
+            if wl == args.workload and n == args.n:
+                continue
+            o, _, _ = measure(args, wl, n, 2, 5, 2, brief=True)
+            others.append(o)
+        out["other_workloads"] = others
     if not args.no_cpu_baseline:
-        del st
-        torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(shape, inp, args.cpu_tokens)
     print(json.dumps(out))
 

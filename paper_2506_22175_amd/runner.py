@@ -89,6 +89,24 @@ class LayerState:
                              self.dW2, self.logits, self.topk_idx, self.topk_w, self.slot, self.counts,
                              self.workspace, [self.s0, self.s1])
 
+    def capture(self):
+        """Record one step into a HIP graph (all launches and the cross-stream events of
+        moe_layer_step are capturable; the library issues no memset nodes).  Returns the graph;
+        call .replay() on it.  The step must have run eagerly once before (kernel attributes)."""
+        torch.cuda.synchronize(self.device)
+        side = torch.cuda.Stream(self.device)
+        keep0 = self.s0
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            self.s0 = side
+            try:
+                with torch.cuda.graph(g, stream=side):
+                    self.step()
+            finally:
+                self.s0 = keep0
+        torch.cuda.synchronize(self.device)
+        return g
+
     def results(self) -> Dict[str, np.ndarray]:
         torch.cuda.synchronize(self.device)
         return dict(y=to_host(self.y), dx=to_host(self.dx), dWg=to_host(self.dWg), dW1=to_host(self.dW1),

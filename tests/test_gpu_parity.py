@@ -308,3 +308,26 @@ def test_kernel_timing_hooks_see_every_gemm(runner):
     assert prof["gemm_fwd1_gelu"][0] == 2 and prof["gemm_nn_store"][0] == 4 and prof["gemm_wgrad"][0] == 4
     assert prof["gemm_dgelu"][0] == 2 and prof["gemm_dgrad"][0] == 2 and prof["dispatch"][0] == 6
     assert all(ms > 0 for cnt, ms in prof.values() if cnt)
+
+
+def test_graph_replay_equals_eager_every_time(runner):
+    """A captured step replayed several times, with eager steps and synchronisations
+    between the replays, gives the eager result each time."""
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=4)
+    st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, 4, s.dtype, 2)
+    st.upload(d)
+    st.zero_grads()
+    st.step()
+    eager = st.results()
+    graph = st.capture()
+    for rep in range(4):
+        st.poison()
+        st.zero_grads()
+        graph.replay()
+        got = st.results()
+        for k_ in ("y", "dx", "dWg", "dW1", "dW2", "slot", "idx", "counts"):
+            assert np.array_equal(got[k_], eager[k_]), (rep, k_)
+        st.zero_grads()
+        st.step()                      # eager work between replays
+        torch.cuda.synchronize()
