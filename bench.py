@@ -153,6 +153,25 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
             gbs = nbytes * per_step * steps / (ms * 1e-3) / 1e9
             hbm[name] = {"launches": l, "avg_us": 1e3 * ms / l, "GB/s": gbs, "frac": gbs / PEAK_HBM_GBS}
 
+    # the same kernels with the schedule serialised on one stream (no GEMM running beside them)
+    hbm_alone = {}
+    if not brief and not args.single_stream:
+        keep = st.s1
+        st.s1 = st.s0
+        B.moe_profile_enable(True)
+        for _ in range(3):
+            st.step()
+        torch.cuda.synchronize()
+        B.moe_profile_enable(False)
+        st.s1 = keep
+        prof1 = B.moe_profile_read()
+        for name, nbytes, per_step in (("dispatch", bytes_dispatch, n_disp_per_step), ("combine", bytes_combine, 1),
+                                       ("dispatch_bwd", bytes_dbwd, 1)):
+            l, ms = prof1[name]
+            if l and ms > 0:
+                gbs = nbytes * per_step * 3 / (ms * 1e-3) / 1e9
+                hbm_alone[name] = {"avg_us": 1e3 * ms / l, "GB/s": gbs, "frac": gbs / PEAK_HBM_GBS}
+
     mem = {}
     for mode in (0, 1, 2):
         cfg = B.make_config(T, M, H, shape.E, k, shape.capacity_factor, n,
@@ -173,7 +192,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
                    "kept_rows": R, "drop_rate": drop_rate},
         "tflops_model": flop_model / (ms_per_step * 1e-3) / 1e12,
         "tflops_executed": flop_exec / (ms_per_step * 1e-3) / 1e12,
-        "roofline": roofline, "hbm_kernels": hbm, "memory_bytes": mem,
+        "roofline": roofline, "hbm_kernels": hbm, "hbm_kernels_alone": hbm_alone, "memory_bytes": mem,
         "other_kernels_ms_per_step": {kd: prof[kd][1] / steps for kd in ("route", "slots", "gate_bwd")},
         "paper_context": "MPipeMoE reports up to 2.8x speedup and up to 47% less memory than FasterMoE on 64 A100 "
                          "GPUs (8 DGX A100); ratios on other hardware, not a target for this number",

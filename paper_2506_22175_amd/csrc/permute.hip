@@ -69,30 +69,149 @@ __global__ __launch_bounds__(PERM_THREADS) void dispatch_kernel(
     }
 }
 
-// y[t] = sum_j w[t,j] * DO[slot[t,j]]  (float accumulation, ascending j)
+// 16 bytes <-> floats (8 bf16 or 4 float)
+template <typename T> struct Unit;
+template <> struct Unit<bf16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void to_float(const uint4& u, float* o) {
+        const unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o[2 * i] = __uint_as_float(w[i] << 16);
+            o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ uint4 from_float(const float* v) {
+        return make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+    }
+};
+template <> struct Unit<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void to_float(const uint4& u, float* o) {
+        o[0] = __uint_as_float(u.x); o[1] = __uint_as_float(u.y); o[2] = __uint_as_float(u.z); o[3] = __uint_as_float(u.w);
+    }
+    static __device__ __forceinline__ uint4 from_float(const float* v) {
+        return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+    }
+};
+
+// y[t] = sum_j w[t,j] * DO[slot[t,j]]  (float accumulation, ascending j).  One wavefront per
+// token; four 16-byte units per lane are in flight per source row.
 template <typename T>
 __global__ __launch_bounds__(PERM_THREADS) void combine_kernel(
     const T* __restrict__ DO, const int* __restrict__ slot, const float* __restrict__ w,
     T* __restrict__ y, int t_begin, int t_count, int M, int k) {
     const int lane = threadIdx.x & 63;
-    const int tl = blockIdx.x * PERM_WAVES + (threadIdx.x >> 6);
+    const int tl = blockIdx.x * PERM_WAVES + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (tl >= t_count) return;
     const int t = t_begin + tl;
+    constexpr int N = Unit<T>::N;
+    const int U = M / N;
     int s[8];
     float ws[8];
     for (int j = 0; j < k; ++j) { s[j] = slot[(size_t)t * k + j]; ws[j] = w[(size_t)t * k + j]; }
-    for (int c = lane * 8; c < M; c += 512) {
-        float acc[8];
+    uint4* out = reinterpret_cast<uint4*>(y + (size_t)t * M);
+    for (int c0 = 0; c0 < U; c0 += 256) {
+        float acc[4][N];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[u][i] = 0.0f;
         for (int j = 0; j < k; ++j) {
             if (s[j] < 0) continue;
-            float r[8];
-            Vec8<T>::load(DO + (size_t)s[j] * M + c, r);
+            const uint4* in = reinterpret_cast<const uint4*>(DO + (size_t)s[j] * M);
+            uint4 v[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = fmaf(ws[j], r[i], acc[i]);
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + u * 64 + lane;
+                v[u] = c < U ? in[c] : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float r[N];
+                Unit<T>::to_float(v[u], r);
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[u][i] = fmaf(ws[j], r[i], acc[u][i]);
+            }
         }
-        Vec8<T>::store(y + (size_t)t * M + c, acc);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * 64 + lane;
+            if (c < U) out[c] = Unit<T>::from_float(acc[u]);
+        }
+    }
+}
+
+// dx[t] = sum_j dDI[slot[t,j]] + dL[t,:] Wg^T with the gate matrix transposed into LDS
+// ([E][M] in the storage type).  One wavefront per token, workgroups walk over tokens.
+constexpr int DXL_THREADS = 512;
+constexpr int DXL_WAVES = DXL_THREADS / 64;
+template <typename T>
+__global__ __launch_bounds__(DXL_THREADS) void dispatch_bwd_lds_kernel(
+    const T* __restrict__ dDI, const int* __restrict__ slot, const float* __restrict__ dL,
+    const T* __restrict__ Wg, T* __restrict__ dx, int t_begin, int t_count, int M, int E, int k) {
+    extern __shared__ __attribute__((aligned(16))) char dxb_smem[];
+    T* wgt = reinterpret_cast<T*>(dxb_smem);                 // wgt[e*M + d]
+    // consecutive lanes take consecutive d of one e: conflict-free LDS writes (the strided
+    // global reads come from L2, the matrix is small)
+    for (int q = threadIdx.x; q < M * E; q += DXL_THREADS) {
+        const int e = q / M, d = q - e * M;
+        wgt[q] = Wg[(size_t)d * E + e];
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int N = Unit<T>::N;
+    const int U = M / N;
+    for (int tl = blockIdx.x * DXL_WAVES + wid; tl < t_count; tl += gridDim.x * DXL_WAVES) {
+        const int t = t_begin + tl;
+        int s[8];
+        for (int j = 0; j < k; ++j) s[j] = slot[(size_t)t * k + j];
+        const float* g = dL + (size_t)t * E;
+        uint4* out = reinterpret_cast<uint4*>(dx + (size_t)t * M);
+        for (int c0 = 0; c0 < U; c0 += 256) {
+            float acc[4][N];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[u][i] = 0.0f;
+            for (int j = 0; j < k; ++j) {
+                if (s[j] < 0) continue;
+                const uint4* in = reinterpret_cast<const uint4*>(dDI + (size_t)s[j] * M);
+                uint4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + u * 64 + lane;
+                    v[u] = c < U ? in[c] : make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    float r[N];
+                    Unit<T>::to_float(v[u], r);
+#pragma unroll
+                    for (int i = 0; i < N; ++i) acc[u][i] += r[i];
+                }
+            }
+            for (int e = 0; e < E; ++e) {
+                const float ge = g[e];
+                const uint4* wrow = reinterpret_cast<const uint4*>(wgt + (size_t)e * M);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + u * 64 + lane;
+                    if (c < U) {
+                        float r[N];
+                        Unit<T>::to_float(wrow[c], r);
+#pragma unroll
+                        for (int i = 0; i < N; ++i) acc[u][i] = fmaf(ge, r[i], acc[u][i]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + u * 64 + lane;
+                if (c < U) out[c] = Unit<T>::from_float(acc[u]);
+            }
+        }
     }
 }
 
@@ -162,8 +281,7 @@ __global__ __launch_bounds__(PERM_THREADS) void dispatch_bwd_kernel(
 // dL[t,e] = p[t,e] * (dp[t,e] - sum_e' dp[t,e'] p[t,e']) with dp nonzero only at the
 // chosen experts; one thread per token.
 __device__ __forceinline__ void gate_dl_token(
-    const float* __restrict__ logits, const int* __restrict__ topk_idx, const int* __restrict__ slot,
-    const float* __restrict__ dw, const float* __restrict__ dw_part, int parts,
+    const float* __restrict__ logits, const int* __restrict__ topk_idx, const float* dw_t,
     float* __restrict__ dL, float* sdl, int t, int E, int k) {
     const float* lg = logits + (size_t)t * E;
     float mx = -INFINITY;
@@ -176,16 +294,8 @@ __device__ __forceinline__ void gate_dl_token(
     float inner = 0.0f;
     for (int j = 0; j < k; ++j) {
         ids[j] = topk_idx[(size_t)t * k + j];
-        float v = 0.0f;
-        if (dw_part) {
-            int s = slot[(size_t)t * k + j];
-            if (s >= 0)
-                for (int c = 0; c < parts; ++c) v += dw_part[(size_t)s * parts + c];
-        } else {
-            v = dw[(size_t)t * k + j];
-        }
-        g[j] = v;
-        inner = fmaf(v, expf(lg[ids[j]] - mx) * inv, inner);
+        g[j] = dw_t[j];
+        inner = fmaf(g[j], expf(lg[ids[j]] - mx) * inv, inner);
     }
     for (int e = 0; e < E; ++e) {
         float p = expf(lg[e] - mx) * inv;
@@ -210,8 +320,31 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
     __shared__ float sdl[DWG_TOK][DWG_EMAX + 1];
     const int tl0 = blockIdx.y * DWG_TOK;
     const int nt = min(DWG_TOK, t_count - tl0);
+    // combine-weight gradients of the block's (token, choice) pairs: either given, or the
+    // fixed-order sum of the GEMM epilogue's column-block partial sums (four lanes per pair)
+    __shared__ float sdw[DWG_TOK * 8];
+    for (int q = threadIdx.x; q < nt * k * 4; q += PERM_THREADS) {
+        const int pair = q >> 2, sub = q & 3;
+        const int ti = pair / k, j = pair - ti * k;
+        const int t = t_begin + tl0 + ti;
+        float v = 0.0f;
+        if (dw_part) {
+            const int sl = slot[(size_t)t * k + j];
+            if (sl >= 0) {
+                const int per = (parts + 3) >> 2;
+                const int c1 = min(parts, (sub + 1) * per);
+                for (int c = sub * per; c < c1; ++c) v += dw_part[(size_t)sl * parts + c];
+            }
+        } else if (sub == 0) {
+            v = dw[(size_t)t * k + j];
+        }
+        v += __shfl_xor(v, 1, 64);
+        v += __shfl_xor(v, 2, 64);
+        if (sub == 0) sdw[pair] = v;
+    }
+    __syncthreads();
     if ((int)threadIdx.x < nt)
-        gate_dl_token(logits, topk_idx, slot, dw, dw_part, parts, dL, sdl[threadIdx.x], t_begin + tl0 + threadIdx.x, E, k);
+        gate_dl_token(logits, topk_idx, sdw + threadIdx.x * k, dL, sdl[threadIdx.x], t_begin + tl0 + threadIdx.x, E, k);
     __syncthreads();
     for (int c = threadIdx.x * 8; c < M; c += PERM_THREADS * 8) {
         for (int e0 = 0; e0 < E; e0 += 16) {
@@ -251,13 +384,24 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
     }
 }
 
+// dWg[i] += sum_b part[b][i]: 32 consecutive outputs per workgroup, eight threads per output
+// each taking every eighth partial block, then a fixed-order sum of the eight.
 __global__ __launch_bounds__(256) void gate_dwg_reduce_kernel(
     const float* __restrict__ part, float* __restrict__ dWg, int nblk, int ME) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= ME) return;
+    __shared__ float red[8][32];
+    const int col = threadIdx.x & 31, sl = threadIdx.x >> 5;
+    const int i = blockIdx.x * 32 + col;
     float s = 0.0f;
-    for (int b = 0; b < nblk; ++b) s += part[(size_t)b * ME + i];
-    dWg[i] += s;
+    if (i < ME)
+        for (int b = sl; b < nblk; b += 8) s += part[(size_t)b * ME + i];
+    red[sl][col] = s;
+    __syncthreads();
+    if (sl == 0 && i < ME) {
+        float tot = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) tot += red[q][col];
+        dWg[i] += tot;
+    }
 }
 
 template <typename T>
@@ -279,6 +423,20 @@ static moe_status dispatch_t(const Dims& d, int part, const void* src, const int
 template <typename T>
 static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const int* slot, const float* dL,
                                  const void* Wg, void* dx, hipStream_t s) {
+    const size_t wg_bytes = (size_t)d.M * d.E * sizeof(T);
+    if (wg_bytes <= 64 * 1024) {
+        auto kern = dispatch_bwd_lds_kernel<T>;
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)wg_bytes));
+        int blocks = (d.Tp + DXL_WAVES - 1) / DXL_WAVES;
+        if (blocks > 512) blocks = 512;          // two workgroups fit on a CU; each walks over its tokens
+        ProfScope ps(PK_DISPATCH_BWD, s);
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(DXL_THREADS), wg_bytes, s, (const T*)dDI, slot, dL,
+                           (const T*)Wg, (T*)dx, part * d.Tp, d.Tp, d.M, d.E, d.k);
+        count_launch(LC_PERMUTE);
+        MOE_CHECK_LAUNCH();
+        return MOE_OK;
+    }
     dim3 grid((d.M / 8 + PERM_THREADS - 1) / PERM_THREADS, (d.Tp + DXB_TOK - 1) / DXB_TOK);
 #define LAUNCH_DXB(EC) hipLaunchKernelGGL((dispatch_bwd_kernel<T, EC>), grid, dim3(PERM_THREADS), 0, s, \
         (const T*)dDI, slot, dL, (const T*)Wg, (T*)dx, part * d.Tp, d.Tp, d.M, d.E, d.k)
@@ -302,7 +460,7 @@ static moe_status gate_bwd_t(const Dims& d, int part, const void* x, const float
                        slot, dw, dw_part, parts, dL, (float*)scratch, part * d.Tp, d.Tp, d.M, d.E, d.k);
     MOE_CHECK_LAUNCH();
     const int ME = d.M * d.E;
-    hipLaunchKernelGGL(gate_dwg_reduce_kernel, dim3((ME + 255) / 256), dim3(256), 0, s,
+    hipLaunchKernelGGL(gate_dwg_reduce_kernel, dim3((ME + 31) / 32), dim3(256), 0, s,
                        (const float*)scratch, dWg, nblk, ME);
     count_launch(LC_OTHER, 2);
     MOE_CHECK_LAUNCH();
