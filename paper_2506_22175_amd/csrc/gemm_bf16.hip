@@ -192,6 +192,17 @@ template <int R, int W, int BK> struct ATile<GEMM_TN, R, W, BK> { typedef NCTile
 template <int LAY, int R, int W, int BK> struct BTile { typedef NCTile<R, W, BK> type; };
 template <int R, int W, int BK> struct BTile<GEMM_NT, R, W, BK> { typedef KCTile<R, W, BK> type; };
 
+struct Unit8 {
+    static __device__ __forceinline__ void to_float(const uint4& u, float* o) {
+        const unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o[2 * i] = __uint_as_float(w[i] << 16);
+            o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+
 // s_waitcnt vmcnt(N) only (N <= 63), with a compiler-level memory fence
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -322,17 +333,21 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     // private LDS region (float, 16-byte chunks XOR-swizzled by row) and picks them up
     // with eight consecutive columns per lane, so that eight lanes cover a whole line of
     // a row: all global reads and writes of the epilogue are 16 or 32 bytes per lane,
-    // row-contiguous.
+    // row-contiguous.  They go through buffer descriptors that end after the last valid
+    // row, so there is no branch: out-of-range reads give zero, out-of-range writes are
+    // dropped, and all reads of a 32-row pass are issued before the arithmetic starts.
     constexpr int CPRW = WN / 8;                 // 8-column pieces per row of the wave's block
     constexpr int NPIECE = 32 * CPRW / 64;       // pieces per lane
     float* stage = reinterpret_cast<float*>(smem + wid * (32 * WN * 4));
     static_assert(C::WAVES * 32 * WN * 4 <= C::LDS_BYTES, "staging does not fit");
-    EpiCtx<bf16_t> c;
-    c.ldc = g.ldc; c.ldz = g.ldz;
-    c.C = (bf16_t*)g.C + (size_t)e * g.c_estride;
-    c.Cf = (float*)g.C + (size_t)e * g.c_estride;
-    c.Z = g.Z ? (bf16_t*)g.Z + (size_t)e * g.Cp * g.ldz : nullptr;
-    c.w = g.slot_w ? g.slot_w + (size_t)e * g.Cp : nullptr;
+    constexpr int CES = (EPI == EPI_ACCUM_F32) ? 4 : 2;       // bytes per output element
+    const char* Cbase = (const char*)g.C + (size_t)e * g.c_estride * CES;
+    const __amdgpu_buffer_rsrc_t rC = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(Cbase), 0, (unsigned)(((size_t)(Mdim - 1) * g.ldc + g.N) * CES), 0x00020000);
+    const bf16_t* Zbase = g.Z ? (const bf16_t*)g.Z + (size_t)e * g.Cp * g.ldz : nullptr;
+    const __amdgpu_buffer_rsrc_t rZ = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(Zbase), 0, Zbase ? (unsigned)(((size_t)(Mdim - 1) * g.ldz + g.N) * 2) : 0u, 0x00020000);
+    const float* wbase = g.slot_w ? g.slot_w + (size_t)e * g.Cp : nullptr;
     const int erow = lane & 31, ehalf = lane >> 5;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -345,23 +360,80 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                 *reinterpret_cast<float4*>(stage + erow * WN + ((cch ^ (erow & 15)) << 2)) = v;
             }
         }
+        // operands of this pass from memory, all requested before any is used
+        int pm[NPIECE];
+        unsigned offC[NPIECE], offZ[NPIECE];
+        uint4 zin[NPIECE];
+        float4 cin0[NPIECE], cin1[NPIECE];
+        float wrow[NPIECE];
+#pragma unroll
+        for (int t = 0; t < NPIECE; ++t) {
+            const int idx = lane + 64 * t;
+            const int row = idx / CPRW, c8 = idx % CPRW;
+            const int m = m0 + wm * WM + i * 32 + row;
+            const int n = n0 + wn * WN + c8 * 8;
+            pm[t] = m;
+            const bool in = n < g.N;             // rows beyond Mdim fall outside the descriptors by themselves
+            offC[t] = in ? (unsigned)(m * g.ldc + n) * CES : OOB_OFFSET;
+            offZ[t] = in ? (unsigned)(m * g.ldz + n) * 2u : OOB_OFFSET;
+            if constexpr (EPI == EPI_DGELU) {
+                zin[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rZ, offZ[t], 0, 0));
+                wrow[t] = m < Mdim ? wbase[m] : 0.0f;
+            }
+            if constexpr (EPI == EPI_ACCUM_F32) {
+                cin0[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, offC[t], 0, 0));
+                cin1[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, offC[t] + 16u, 0, 0));
+            }
+        }
 #pragma unroll
         for (int t = 0; t < NPIECE; ++t) {
             const int idx = lane + 64 * t;
             const int row = idx / CPRW, c8 = idx % CPRW;
             const float4 lo = *reinterpret_cast<const float4*>(stage + row * WN + (((2 * c8) ^ (row & 15)) << 2));
             const float4 hi = *reinterpret_cast<const float4*>(stage + row * WN + (((2 * c8 + 1) ^ (row & 15)) << 2));
-            const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            const int m = m0 + wm * WM + i * 32 + row;
-            const int n = n0 + wn * WN + c8 * 8;
-            float dot = 0.0f;
-            if (m < Mdim && n < g.N) dot = epilogue8<bf16_t, EPI>(c, m, n, v);
-            if (EPI == EPI_DGELU && g.dw_part) {
-                // the CPRW lanes of a row are neighbours
+            float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            if constexpr (EPI == EPI_STORE) {
+                uint4 o = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o), rC, offC[t], 0, 0);
+            } else if constexpr (EPI == EPI_GELU) {
+                float z[8], a[8];
 #pragma unroll
-                for (int off = CPRW / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
-                if (c8 == 0 && m < Mdim)
-                    g.dw_part[((size_t)e * g.Cp + m) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
+                for (int q = 0; q < 8; ++q) { z[q] = bf16_to_f32(f32_to_bf16(v[q])); a[q] = gelu_f(z[q]); }
+                uint4 oz = make_uint4(pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3]), pack_bf16x2(z[4], z[5]), pack_bf16x2(z[6], z[7]));
+                uint4 oa = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
+                if (Zbase) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oz), rZ, offZ[t], 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oa), rC, offC[t], 0, 0);
+            } else if constexpr (EPI == EPI_DGELU) {
+                float z[8], dz[8], a[8];
+                Unit8::to_float(zin[t], z);
+                const float w = wrow[t];
+                float dot = 0.0f;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    float gq, dg;
+                    gelu_both_f(z[q], &gq, &dg);
+                    dot = fmaf(gq, v[q], dot);
+                    a[q] = w * gq;
+                    dz[q] = w * v[q] * dg;
+                }
+                uint4 od = make_uint4(pack_bf16x2(dz[0], dz[1]), pack_bf16x2(dz[2], dz[3]), pack_bf16x2(dz[4], dz[5]), pack_bf16x2(dz[6], dz[7]));
+                uint4 oa = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, od), rC, offC[t], 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oa), rZ, offZ[t], 0, 0);
+                if (g.dw_part) {
+                    // the CPRW lanes of a row are neighbours; rows and columns out of range gave zeros
+                    if (!(pm[t] < Mdim && offC[t] != OOB_OFFSET)) dot = 0.0f;
+#pragma unroll
+                    for (int off = CPRW / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
+                    if (c8 == 0 && pm[t] < Mdim)
+                        g.dw_part[((size_t)e * g.Cp + pm[t]) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
+                }
+            } else {
+                float4 o0 = cin0[t], o1 = cin1[t];
+                o0.x += v[0]; o0.y += v[1]; o0.z += v[2]; o0.w += v[3];
+                o1.x += v[4]; o1.y += v[5]; o1.z += v[6]; o1.w += v[7];
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o0), rC, offC[t], 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o1), rC, offC[t] + 16u, 0, 0);
             }
         }
     }
@@ -371,7 +443,9 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
 #ifndef MOE_GEMM_CFG
 #define MOE_GEMM_CFG 3
 #endif
-#if MOE_GEMM_CFG == 2
+#if MOE_GEMM_CFG == 0
+typedef TileCfg<256, 256, 64, 2, 2, 2, 1> Cfg;     // 4 waves of 128x128, ring of 2 x 64 k
+#elif MOE_GEMM_CFG == 2
 typedef TileCfg<256, 256, 32, 5, 2, 4, 2> Cfg;     // 8 waves of 128x64, ring of 5 x 32 k
 #elif MOE_GEMM_CFG == 3
 typedef TileCfg<256, 256, 64, 2, 2, 4, 2> Cfg;     // 8 waves of 128x64, ring of 2 x 64 k
