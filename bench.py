@@ -69,7 +69,8 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
     shape = synth.WORKLOADS[workload]
     inp = synth.make_inputs(shape, seed=0)
     st = runner.LayerState(shape.T, shape.M, shape.H, shape.E, shape.k, shape.capacity_factor, n,
-                           shape.dtype, reuse, second_stream=not args.single_stream)
+                           shape.dtype, reuse, second_stream=not args.single_stream,
+                           grad_overwrite=0 if args.accumulate else 1)
     st.upload(inp)
     st.zero_grads()
     torch.cuda.reset_peak_memory_stats()
@@ -189,6 +190,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
         "config": {"workload": f"{shape.name}: T={T} M={M} H={H} E={shape.E} k={k} cf={shape.capacity_factor}",
                    "n_partitions": n, "reuse_mode": reuse, "streams": 1 if args.single_stream else 2,
                    "hip_graph": bool(args.graph),
+                   "weight_grads": "accumulated into zeroed buffers" if args.accumulate else "overwritten each step",
                    "kept_rows": R, "drop_rate": drop_rate},
         "tflops_model": flop_model / (ms_per_step * 1e-3) / 1e12,
         "tflops_executed": flop_exec / (ms_per_step * 1e-3) / 1e12,
@@ -219,6 +221,8 @@ def main():
     ap.add_argument("--single-stream", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=2048)
     ap.add_argument("--graph", action="store_true", help="replay a captured HIP graph of the step (no per-kernel timing)")
+    ap.add_argument("--accumulate", action="store_true",
+                    help="weight gradients are added to the buffers (default: each step overwrites them)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the short runs of the other workloads")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -62,6 +62,10 @@ typedef struct {
     int32_t n_partitions;
     int32_t dtype;   /* moe_dtype */
     int32_t reuse;   /* moe_reuse */
+    int32_t grad_overwrite; /* 0: dWg, dW1, dW2 are accumulated into (caller zeroes them);
+                               1: calls for partition 0 store, calls for later partitions
+                               accumulate, so one pass over partitions 0..n-1 leaves the
+                               gradients of this step whatever the buffers held before */
 } moe_config;
 
 /* Host only.  C_p = ceil(capacity_factor * k * (T / n) / E), evaluated in double
@@ -127,7 +131,8 @@ moe_status moe_expert_ffn_fwd(const moe_config* cfg, int32_t part, const void* D
  *   dZ = slot_w * G * gelu'(Z);  Z is overwritten with slot_w * gelu(Z);
  *   dW2[e] += (slot_w gelu(Z))^T dDO;  dDI = dZ W1[e]^T;  dW1[e] += DI^T dZ.
  *   Z [R_p,H] in/out (input ignored when recompute); dZ [R_p,H] scratch;
- *   dDI [R_p,M] out; dW1 [E,M,H], dW2 [E,H,M] float, accumulated into;
+ *   dDI [R_p,M] out; dW1 [E,M,H], dW2 [E,H,M] float, accumulated into (stored
+ *   when cfg->grad_overwrite and part == 0; an expert without rows then gets zeros);
  *   dw_part [R_p, moe_dw_parts(cfg)] float out, may be NULL. */
 moe_status moe_expert_ffn_bwd(const moe_config* cfg, int32_t part, int32_t recompute,
                               const void* DI, void* Z, const void* dDO, const int32_t* counts,
@@ -142,7 +147,8 @@ moe_status moe_combine(const moe_config* cfg, int32_t part, const void* DO, cons
                        const float* topk_w, void* y, void* stream);
 
 /* Gate backward of partition `part`: dL = softmax Jacobian applied to the
- * combine-weight gradients, dWg += x^T dL (two-stage, fixed order).
+ * combine-weight gradients, dWg += x^T dL (two-stage, fixed order; dWg = x^T dL
+ * when cfg->grad_overwrite and part == 0).
  *   dw [T,k] float (used when dw_part is NULL) or dw_part [R_p, parts] summed in
  *   ascending c; dL [T,E] float out; scratch: moe_gate_scratch_bytes(cfg). */
 moe_status moe_gate_bwd(const moe_config* cfg, int32_t part, const void* x, const float* logits,
@@ -162,7 +168,8 @@ moe_status moe_dispatch_bwd(const moe_config* cfg, int32_t part, const void* dDI
  * caller synchronises streams[0] only.  n_streams must be >= 2 (both may be the
  * same stream, which serialises the schedule).
  *   x, dy [T,M]; y, dx [T,M] out; dWg [M,E], dW1 [E,M,H], dW2 [E,H,M] float,
- *   accumulated into (caller zeroes); logits [T,E], topk_idx, topk_w, slot
+ *   accumulated into (caller zeroes) or, with cfg->grad_overwrite, overwritten;
+ *   logits [T,E], topk_idx, topk_w, slot
  *   [T,k], counts [n,E] out; workspace of moe_workspace_bytes(cfg). */
 moe_status moe_layer_step(const moe_config* cfg, const void* x, const void* dy,
                           const void* Wg, const float* gate_bias, const void* W1, const void* W2,

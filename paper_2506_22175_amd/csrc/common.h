@@ -93,6 +93,7 @@ __device__ __forceinline__ float gelu_f(float z) {
 struct Dims {
     int T, M, H, E, k, n, Tp, Cp, Rp;
     int dtype, reuse;
+    int overwrite;   // weight gradients are overwritten (first partition stores) instead of accumulated
     size_t es;   // element size in bytes
 };
 
@@ -138,7 +139,8 @@ enum GemmEpilogue {
     EPI_STORE = 0,      // C = acc                       (element type)
     EPI_GELU = 1,       // Z = acc (optional), A = gelu(Z)
     EPI_DGELU = 2,      // dZ = w*acc*gelu'(Z), Z <- w*gelu(Z), dw_part = <gelu(Z), acc>
-    EPI_ACCUM_F32 = 3   // C(float) += acc
+    EPI_ACCUM_F32 = 3,  // C(float) += acc
+    EPI_STORE_F32 = 4   // C(float) = acc (also where the reduction is empty)
 };
 
 struct GemmArgs {
@@ -160,7 +162,7 @@ struct GemmArgs {
 inline int gemm_prof_kind(int lay, int epi) {
     if (epi == EPI_GELU) return PK_GEMM_FWD1;
     if (epi == EPI_DGELU) return PK_GEMM_DGELU;
-    if (epi == EPI_ACCUM_F32) return PK_GEMM_WGRAD;
+    if (epi == EPI_ACCUM_F32 || epi == EPI_STORE_F32) return PK_GEMM_WGRAD;
     return lay == GEMM_NN ? PK_GEMM_NN : PK_GEMM_DGRAD;
 }
 

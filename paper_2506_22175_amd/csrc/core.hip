@@ -25,6 +25,7 @@ moe_status make_dims(const moe_config* cfg, Dims* d) {
     d->Cp = (int)c;
     d->Rp = d->Cp * d->E;
     d->dtype = cfg->dtype; d->reuse = cfg->reuse;
+    d->overwrite = cfg->grad_overwrite != 0;
     d->es = cfg->dtype == MOE_F32 ? 4 : 2;
     return MOE_OK;
 }

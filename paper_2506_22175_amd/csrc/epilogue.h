@@ -74,54 +74,14 @@ __device__ __forceinline__ float epilogue4(const EpiCtx<T>& c, int r, int n, con
         Vec4<T>::store(c.C + (size_t)r * c.ldc + n, dz);
         Vec4<T>::store(c.Z + (size_t)r * c.ldz + n, a);
         return dot;
+    } else if constexpr (EPI == EPI_STORE_F32) {
+        *reinterpret_cast<float4*>(c.Cf + (size_t)r * c.ldc + n) = make_float4(v[0], v[1], v[2], v[3]);
+        return 0.0f;
     } else {
         float* p = c.Cf + (size_t)r * c.ldc + n;
         float4 o = *reinterpret_cast<float4*>(p);
         o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
         *reinterpret_cast<float4*>(p) = o;
-        return 0.0f;
-    }
-}
-
-// Same epilogues for eight consecutive columns of one row (16 bytes of bf16, 32 of float):
-// used where the accumulators have been re-laid through LDS so that eight lanes cover a
-// whole 128-byte line of the row.
-template <typename T, int EPI>
-__device__ __forceinline__ float epilogue8(const EpiCtx<T>& c, int r, int n, const float* v) {
-    if constexpr (EPI == EPI_STORE) {
-        Vec8<T>::store(c.C + (size_t)r * c.ldc + n, v);
-        return 0.0f;
-    } else if constexpr (EPI == EPI_GELU) {
-        float z[8], a[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) { z[i] = Vec4<T>::round(v[i]); a[i] = gelu_f(z[i]); }
-        if (c.Z) Vec8<T>::store(c.Z + (size_t)r * c.ldz + n, z);
-        Vec8<T>::store(c.C + (size_t)r * c.ldc + n, a);
-        return 0.0f;
-    } else if constexpr (EPI == EPI_DGELU) {
-        float z[8], dz[8], a[8];
-        Vec8<T>::load(c.Z + (size_t)r * c.ldz + n, z);
-        const float w = c.w[r];
-        float dot = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            float g, dg;
-            gelu_both_f(z[i], &g, &dg);
-            dot = fmaf(g, v[i], dot);
-            a[i] = w * g;
-            dz[i] = w * v[i] * dg;
-        }
-        Vec8<T>::store(c.C + (size_t)r * c.ldc + n, dz);
-        Vec8<T>::store(c.Z + (size_t)r * c.ldz + n, a);
-        return dot;
-    } else {
-        float* p = c.Cf + (size_t)r * c.ldc + n;
-        float4 o0 = *reinterpret_cast<float4*>(p);
-        float4 o1 = *reinterpret_cast<float4*>(p + 4);
-        o0.x += v[0]; o0.y += v[1]; o0.z += v[2]; o0.w += v[3];
-        o1.x += v[4]; o1.y += v[5]; o1.z += v[6]; o1.w += v[7];
-        *reinterpret_cast<float4*>(p) = o0;
-        *reinterpret_cast<float4*>(p + 4) = o1;
         return 0.0f;
     }
 }

@@ -70,7 +70,7 @@ moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void*
         a.B = dDO; a.ldb = d.M; a.b_estride = eM;
         a.C = dW2; a.ldc = d.M; a.c_estride = wMH;
         a.N = d.M;
-        MOE_TRY(run_gemm(d, GEMM_TN, EPI_ACCUM_F32, a, s));
+        MOE_TRY(run_gemm(d, GEMM_TN, (d.overwrite && part == 0) ? EPI_STORE_F32 : EPI_ACCUM_F32, a, s));
     }
     {   // dDI = dZ W1^T
         GemmArgs a = base_args(d, cp);
@@ -86,7 +86,7 @@ moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void*
         a.B = dZ; a.ldb = d.H; a.b_estride = eH;
         a.C = dW1; a.ldc = d.H; a.c_estride = wMH;
         a.N = d.H;
-        MOE_TRY(run_gemm(d, GEMM_TN, EPI_ACCUM_F32, a, s));
+        MOE_TRY(run_gemm(d, GEMM_TN, (d.overwrite && part == 0) ? EPI_STORE_F32 : EPI_ACCUM_F32, a, s));
     }
     return MOE_OK;
 }

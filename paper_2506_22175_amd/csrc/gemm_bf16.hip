@@ -100,7 +100,7 @@ struct KCTile {
     __device__ __forceinline__ void init(const bf16_t* P, int ld, int row0, int row_limit, int K_, int lane, int wid) {
         const int valid = min(R, row_limit - row0);
         K = K_;
-        rsrc = make_rsrc(P + (size_t)row0 * ld, (unsigned)(((size_t)(valid - 1) * ld + K_) * 2));
+        rsrc = make_rsrc(P + (size_t)row0 * ld, K_ > 0 ? (unsigned)(((size_t)(valid - 1) * ld + K_) * 2) : 0u);
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int q = wid * NI + j;
@@ -148,7 +148,7 @@ struct NCTile {
     // P: operand base of this expert ([k][n], n contiguous); rows [0, K) x columns [n0, n_limit) valid
     __device__ __forceinline__ void init(const bf16_t* P, int ld, int n0, int n_limit, int K, int lane, int wid) {
         const int n_valid = n_limit - n0;
-        rsrc = make_rsrc(P + n0, (unsigned)(((size_t)(K - 1) * ld + n_valid) * 2));
+        rsrc = make_rsrc(P + n0, K > 0 ? (unsigned)(((size_t)(K - 1) * ld + n_valid) * 2) : 0u);
         kstep = (unsigned)ld * 2u;
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
@@ -256,7 +256,8 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     int Mdim, Kdim;
     if (LAY == GEMM_TN) { Mdim = g.Mo; Kdim = rows; } else { Mdim = rows; Kdim = g.K; }
     const int m0 = tm * BM, n0 = tn * BN;
-    if (m0 >= Mdim || Kdim <= 0) return;
+    if (m0 >= Mdim) return;
+    if (Kdim <= 0 && EPI != EPI_STORE_F32) return;    // nothing to add; a plain store still writes zeros
 
     const bf16_t* A = (const bf16_t*)g.A + (size_t)e * g.a_estride;
     const bf16_t* B = (const bf16_t*)g.B + (size_t)e * g.b_estride;
@@ -340,7 +341,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     constexpr int NPIECE = 32 * CPRW / 64;       // pieces per lane
     float* stage = reinterpret_cast<float*>(smem + wid * (32 * WN * 4));
     static_assert(C::WAVES * 32 * WN * 4 <= C::LDS_BYTES, "staging does not fit");
-    constexpr int CES = (EPI == EPI_ACCUM_F32) ? 4 : 2;       // bytes per output element
+    constexpr int CES = (EPI == EPI_ACCUM_F32 || EPI == EPI_STORE_F32) ? 4 : 2;   // bytes per output element
     const char* Cbase = (const char*)g.C + (size_t)e * g.c_estride * CES;
     const __amdgpu_buffer_rsrc_t rC = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<char*>(Cbase), 0, (unsigned)(((size_t)(Mdim - 1) * g.ldc + g.N) * CES), 0x00020000);
@@ -428,6 +429,9 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                     if (c8 == 0 && pm[t] < Mdim)
                         g.dw_part[((size_t)e * g.Cp + pm[t]) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
                 }
+            } else if constexpr (EPI == EPI_STORE_F32) {
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, lo), rC, offC[t], 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, hi), rC, offC[t] + 16u, 0, 0);
             } else {
                 float4 o0 = cin0[t], o1 = cin1[t];
                 o0.x += v[0]; o0.y += v[1]; o0.z += v[2]; o0.w += v[3];
@@ -486,6 +490,7 @@ static moe_status launch_lay(GemmEpilogue epi, const GemmArgs& a, hipStream_t s)
         case EPI_GELU: return launch_one<LAY, EPI_GELU, Cfg>(a, s);
         case EPI_DGELU: return launch_one<LAY, EPI_DGELU, Cfg>(a, s);
         case EPI_ACCUM_F32: return launch_one<LAY, EPI_ACCUM_F32, Cfg>(a, s);
+        case EPI_STORE_F32: return launch_one<LAY, EPI_STORE_F32, Cfg>(a, s);
     }
     return MOE_ERR_UNSUPPORTED;
 }

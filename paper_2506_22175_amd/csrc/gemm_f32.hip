@@ -100,6 +100,7 @@ static moe_status launch_f32(GemmEpilogue epi, const GemmArgs& a, hipStream_t s)
         case EPI_GELU: hipLaunchKernelGGL((gemm_f32_kernel<LAY, EPI_GELU>), grid, block, 0, s, a, tiles_m, tiles_n); break;
         case EPI_DGELU: hipLaunchKernelGGL((gemm_f32_kernel<LAY, EPI_DGELU>), grid, block, 0, s, a, tiles_m, tiles_n); break;
         case EPI_ACCUM_F32: hipLaunchKernelGGL((gemm_f32_kernel<LAY, EPI_ACCUM_F32>), grid, block, 0, s, a, tiles_m, tiles_n); break;
+        case EPI_STORE_F32: hipLaunchKernelGGL((gemm_f32_kernel<LAY, EPI_STORE_F32>), grid, block, 0, s, a, tiles_m, tiles_n); break;
     }
     count_launch(LC_GEMM);
     MOE_CHECK_LAUNCH();

@@ -387,7 +387,7 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
 // dWg[i] += sum_b part[b][i]: 32 consecutive outputs per workgroup, eight threads per output
 // each taking every eighth partial block, then a fixed-order sum of the eight.
 __global__ __launch_bounds__(256) void gate_dwg_reduce_kernel(
-    const float* __restrict__ part, float* __restrict__ dWg, int nblk, int ME) {
+    const float* __restrict__ part, float* __restrict__ dWg, int nblk, int ME, int store) {
     __shared__ float red[8][32];
     const int col = threadIdx.x & 31, sl = threadIdx.x >> 5;
     const int i = blockIdx.x * 32 + col;
@@ -400,7 +400,7 @@ __global__ __launch_bounds__(256) void gate_dwg_reduce_kernel(
         float tot = 0.0f;
 #pragma unroll
         for (int q = 0; q < 8; ++q) tot += red[q][col];
-        dWg[i] += tot;
+        dWg[i] = store ? tot : dWg[i] + tot;
     }
 }
 
@@ -461,7 +461,7 @@ static moe_status gate_bwd_t(const Dims& d, int part, const void* x, const float
     MOE_CHECK_LAUNCH();
     const int ME = d.M * d.E;
     hipLaunchKernelGGL(gate_dwg_reduce_kernel, dim3((ME + 31) / 32), dim3(256), 0, s,
-                       (const float*)scratch, dWg, nblk, ME);
+                       (const float*)scratch, dWg, nblk, ME, (d.overwrite && part == 0) ? 1 : 0);
     count_launch(LC_OTHER, 2);
     MOE_CHECK_LAUNCH();
     return MOE_OK;

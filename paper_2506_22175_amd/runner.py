@@ -29,10 +29,10 @@ class LayerState:
     """All device buffers of one layer step for a given configuration."""
 
     def __init__(self, T, M, H, E, k, capacity_factor, n_partitions=1, dtype="bf16", reuse=0, device="cuda:0",
-                 second_stream: bool = True):
+                 second_stream: bool = True, grad_overwrite: int = 0):
         self.dtype = dtype
         self.device = device
-        self.cfg = B.make_config(T, M, H, E, k, capacity_factor, n_partitions, _MOE_DT[dtype], reuse)
+        self.cfg = B.make_config(T, M, H, E, k, capacity_factor, n_partitions, _MOE_DT[dtype], reuse, grad_overwrite)
         self.C_p = B.moe_capacity(self.cfg)
         self.ws_total, self.ws_saved, self.ws_temp, self.ws_routing = B.moe_workspace_bytes(self.cfg)
         td = _TORCH_DT[dtype]

@@ -159,6 +159,33 @@ def test_repeated_steps_reuse_the_workspace_cleanly(oracle, runner):
     assert relerr(b["dWg"], 2.0 * a["dWg"]) <= 1e-6
 
 
+@pytest.mark.parametrize("case", ["small", "skew_empty_experts_bf16", "ragged_f32", "min_dims_bf16"])
+def test_grad_overwrite_equals_accumulation_from_zero(runner, case):
+    """With grad_overwrite the first partition stores the weight gradients, so buffers
+    full of NaN give what accumulation into zeroed buffers gives, bit for bit; an
+    expert without rows in partition 0 still gets its zeros written."""
+    if case == "small":
+        s, n = synth.WORKLOADS["small"], 4
+    else:
+        name, T, M, H, E, k, cf, dt, n, zipf = next(c for c in CASES if c[0] == case)
+        kw = dict(zipf_s=1.2, zipf_tau=zipf) if zipf else {}
+        s = synth.custom_shape(T, M, H, E, k, cf, dtype=dt, x_std=1.0, w_std=0.05, name=name, **kw)
+    d = synth.make_inputs(s, seed=3)
+    base = runner.run_layer_step(s, d, n, 2)
+    st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, n, s.dtype, 2, grad_overwrite=1)
+    st.upload(d)
+    st.poison()
+    for t in (st.dWg, st.dW1, st.dW2):
+        t.fill_(float("nan"))
+    for _ in range(2):                        # the second step overwrites the first one's result
+        st.step()
+        g = st.results()
+        for k_ in ("y", "dx", "dWg", "dW1", "dW2"):
+            assert np.array_equal(g[k_], base[k_]), k_
+    if case.startswith("skew"):
+        assert (base["counts"][0] == 0).any(), "case is meant to leave an expert empty in partition 0"
+
+
 # ---------------------------------------------------------------------------------
 # the large workloads: routing on everything, values on samples
 # ---------------------------------------------------------------------------------
