@@ -71,6 +71,8 @@ struct TileCfg {
     static constexpr int TM = WM / 32, TN = WN / 32;
     static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
     static constexpr int LDS_BYTES = NS * STAGE_BYTES;
+    // one wave per SIMD: the main loop is written out instruction by instruction
+    static constexpr bool PIPE = (WAVES == 4 && OCC == 1 && BK == 32 && NS == 5 && TM == 4 && TN == 4);
     static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds the CU's 160 KB");
     static_assert(BK == 32 || BK == 64, "tile depth");
 };
@@ -110,12 +112,13 @@ struct KCTile {
             voff[j] = (unsigned)(row * ld + c * 8) * 2u;
         }
     }
+    __device__ __forceinline__ void load_one(char* tile, int k0, int wid, int j) const {
+        const int q = wid * NI + j;
+        load_to_lds(rsrc, lds_address(tile) + q * 1024, (k0 + kc[j] < K) ? voff[j] + (unsigned)k0 * 2u : OOB_OFFSET);
+    }
     __device__ __forceinline__ void load(char* tile, int k0, int wid) const {
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int q = wid * NI + j;
-            load_to_lds(rsrc, lds_address(tile) + q * 1024, (k0 + kc[j] < K) ? voff[j] + (unsigned)k0 * 2u : OOB_OFFSET);
-        }
+        for (int j = 0; j < NI; ++j) load_one(tile, k0, wid, j);
     }
     // fragment of the 32 rows starting at rb: lane reads row rb + lane%32, k = 16*kk + 8*(lane/32) .. +7
     struct Frag {
@@ -158,12 +161,13 @@ struct NCTile {
             voff[j] = (u * 8 < n_valid) ? (unsigned)(row * ld + u * 8) * 2u : OOB_OFFSET;
         }
     }
+    __device__ __forceinline__ void load_one(char* tile, int k0, int wid, int j) const {
+        const int q = wid * NI + j;
+        load_to_lds(rsrc, lds_address(tile) + q * 1024, voff[j] + (unsigned)k0 * kstep);
+    }
     __device__ __forceinline__ void load(char* tile, int k0, int wid) const {
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int q = wid * NI + j;
-            load_to_lds(rsrc, lds_address(tile) + q * 1024, voff[j] + (unsigned)k0 * kstep);
-        }
+        for (int j = 0; j < NI; ++j) load_one(tile, k0, wid, j);
     }
     // fragment of the 32 columns starting at nb: two transposing reads give the lane
     // n = nb + lane%32, k = 16*kk + 8*(lane/32) .. +7.  In a 16-lane group lane a points at
@@ -209,6 +213,14 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
     asm volatile("" ::: "memory");
+}
+
+// The matrix instruction as volatile assembly with a memory clobber: the compiler keeps
+// such statements, the LDS reads and the loads into LDS in the order they are written,
+// which is what the hand-scheduled loop below relies on (it still allocates registers
+// and inserts the s_waitcnt lgkmcnt for LDS reads it issued itself).
+__device__ __forceinline__ void mfma_pinned(floatx16& acc, const bf16x8& a, const bf16x8& b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b) : "memory");
 }
 
 template <int LAY, int EPI, typename C>
@@ -287,41 +299,106 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // Ring of NS stages.  Tiles 0 .. NS-2 are requested up front; in iteration kt
-    // the wave waits until its own part of tile kt has landed (the NS-2 younger
-    // tiles may still be in flight), the barrier makes every wave's part visible
-    // and tells that tile kt-1 has been consumed, whose stage then receives tile
-    // kt+NS-1.  A tile past the end reads as zeros.
     constexpr int LPW = AT::NI + BT::NI;         // loads per wave per tile
+    if constexpr (C::PIPE) {
+        // One wave per SIMD, so nothing hides a stall: every LDS read and every load into
+        // LDS sits between two matrix instructions, one per instruction, and the data a
+        // block of 16 matrix instructions needs was requested during the block before.
+        // A tile is 32 k = two such blocks; the ring holds five tiles.  In iteration t
+        //   block 0 multiplies k 0..15 of tile t, reads k 16..31 of it into the second
+        //           fragment set and requests the second half of tile t+4;
+        //   then the wave waits for its part of tile t+1 and meets the others (their
+        //           parts have landed too, and nobody reads stage t any more);
+        //   block 1 multiplies k 16..31, reads k 0..15 of tile t+1 into the first
+        //           fragment set and requests the first half of tile t+5 into stage t.
+        // Up to four tiles (128 KB) are in flight towards a CU.
+        static_assert(LPW == 8 && AT::NI == 4 && BT::NI == 4, "load schedule below assumes 4 + 4 loads per wave per tile");
+        auto request = [&](char* st, int k0, int l) {          // load l (0..7) of the tile starting at k0
+            if (l < AT::NI) ta.load_one(st, k0, wid, l);
+            else tb.load_one(st + A_BYTES, k0, wid, l - AT::NI);
+        };
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) {
-        ta.load(smem + s * STAGE, s * BK, wid);
-        tb.load(smem + s * STAGE + A_BYTES, s * BK, wid);
-    }
-    int st_cur = 0, st_free = NS - 1;
-    for (int kt = 0; kt < KT; ++kt) {
-        wait_vmcnt<(NS - 2) * LPW>();
+        for (int s = 0; s < NS - 1; ++s)
+#pragma unroll
+            for (int l = 0; l < LPW; ++l) request(smem + s * STAGE, s * BK, l);
+#pragma unroll
+        for (int l = 0; l < LPW / 2; ++l) request(smem + (NS - 1) * STAGE, (NS - 1) * BK, l);
+        wait_vmcnt<3 * LPW + LPW / 2>();                        // tile 0 is in
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        char* cur = smem + st_cur * STAGE;
-        char* nxt = smem + st_free * STAGE;
-        ta.load(nxt, (kt + NS - 1) * BK, wid);
-        tb.load(nxt + A_BYTES, (kt + NS - 1) * BK, wid);
+        bf16x8 F0[8], F1[8];
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 af[TM], bfr[TNN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = fa[i].read(cur, kk);
-#pragma unroll
-            for (int j = 0; j < TNN; ++j) bfr[j] = fb[j].read(cur + A_BYTES, kk);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TNN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        for (int f = 0; f < 4; ++f) {
+            F0[f] = fa[f].read(smem, 0);
+            F0[4 + f] = fb[f].read(smem + A_BYTES, 0);
         }
-        st_free = st_cur;
-        st_cur = (st_cur + 1 == NS) ? 0 : st_cur + 1;
+        int st = 0;
+#pragma unroll 1
+        for (int kt = 0; kt < KT; ++kt) {
+            char* cur = smem + st * STAGE;
+            const int stn = (st + 1 == NS) ? 0 : st + 1;
+            const int stp = (st == 0) ? NS - 1 : st - 1;
+            char* nxt = smem + stn * STAGE;
+            char* prv = smem + stp * STAGE;
+#pragma unroll
+            for (int m = 0; m < 16; ++m) {
+                mfma_pinned(acc[m >> 2][m & 3], F0[4 + (m & 3)], F0[m >> 2]);
+                if (m < 4) F1[m] = fa[m].read(cur, 1);
+                else if (m < 8) F1[m] = fb[m - 4].read(cur + A_BYTES, 1);
+                else if (m < 12) request(prv, (kt + 4) * BK, LPW / 2 + m - 8);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave no longer reads stage t
+            wait_vmcnt<3 * LPW>();                               // its part of tile t+1 is in
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int m = 0; m < 16; ++m) {
+                mfma_pinned(acc[m >> 2][m & 3], F1[4 + (m & 3)], F1[m >> 2]);
+                if (m < 4) F0[m] = fa[m].read(nxt, 0);
+                else if (m < 8) F0[m] = fb[m - 4].read(nxt + A_BYTES, 0);
+                else if (m < 12) request(cur, (kt + 5) * BK, m - 8);
+            }
+            st = stn;
+        }
+        // the assembler-level matrix instructions are invisible to the compiler's hazard
+        // checks: let the last of them retire before anything reads the accumulators
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    } else {
+        // Ring of NS stages.  Tiles 0 .. NS-2 are requested up front; in iteration kt
+        // the wave waits until its own part of tile kt has landed (the NS-2 younger
+        // tiles may still be in flight), the barrier makes every wave's part visible
+        // and tells that tile kt-1 has been consumed, whose stage then receives tile
+        // kt+NS-1.  A tile past the end reads as zeros.
+    #pragma unroll
+        for (int s = 0; s < NS - 1; ++s) {
+            ta.load(smem + s * STAGE, s * BK, wid);
+            tb.load(smem + s * STAGE + A_BYTES, s * BK, wid);
+        }
+        int st_cur = 0, st_free = NS - 1;
+        for (int kt = 0; kt < KT; ++kt) {
+            wait_vmcnt<(NS - 2) * LPW>();
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            char* cur = smem + st_cur * STAGE;
+            char* nxt = smem + st_free * STAGE;
+            ta.load(nxt, (kt + NS - 1) * BK, wid);
+            tb.load(nxt + A_BYTES, (kt + NS - 1) * BK, wid);
+    #pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) {
+                bf16x8 af[TM], bfr[TNN];
+    #pragma unroll
+                for (int i = 0; i < TM; ++i) af[i] = fa[i].read(cur, kk);
+    #pragma unroll
+                for (int j = 0; j < TNN; ++j) bfr[j] = fb[j].read(cur + A_BYTES, kk);
+    #pragma unroll
+                for (int i = 0; i < TM; ++i)
+    #pragma unroll
+                    for (int j = 0; j < TNN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+            }
+            st_free = st_cur;
+            st_cur = (st_cur + 1 == NS) ? 0 : st_cur + 1;
+        }
     }
     wait_vmcnt<0>();                             // nothing of this workgroup is in flight into LDS any more
     __builtin_amdgcn_s_barrier();                // and every wave is done reading the ring
@@ -443,23 +520,34 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     }
 }
 
-// Tile shape in use.  MOE_GEMM_CFG selects it at build time for experiments.
+// Tile shapes in use.  Both cover 256 x 256 per workgroup (the L2-to-CU traffic per
+// flop that the chip can sustain asks for no less).  The four-wave shape reads a third
+// less from LDS and has the hand-scheduled loop; it wins where the loop dominates
+// (K = H, and the weight-gradient GEMMs).  The eight-wave shape keeps two waves per
+// SIMD, which hides the latencies of the arithmetic-heavy GeLU epilogues better; it
+// wins for the K = M GEMMs that carry them.  MOE_GEMM_CFG overrides the choice at
+// build time for experiments (3: eight waves everywhere, 6: four waves everywhere).
+typedef TileCfg<256, 256, 64, 2, 2, 4, 2> Cfg8;    // 8 waves of 128x64, ring of 2 x 64 k
+typedef TileCfg<256, 256, 32, 5, 2, 2, 1> Cfg4;    // 4 waves of 128x128, ring of 5 x 32 k, hand-scheduled loop
 #ifndef MOE_GEMM_CFG
-#define MOE_GEMM_CFG 3
+#define MOE_GEMM_CFG 0
 #endif
+template <int EPI> struct CfgFor {
+#if MOE_GEMM_CFG == 3
+    typedef Cfg8 type;
+#elif MOE_GEMM_CFG == 6
+    typedef Cfg4 type;
+#else
+    typedef Cfg4 type;
+#endif
+};
 #if MOE_GEMM_CFG == 0
-typedef TileCfg<256, 256, 64, 2, 2, 2, 1> Cfg;     // 4 waves of 128x128, ring of 2 x 64 k
-#elif MOE_GEMM_CFG == 2
-typedef TileCfg<256, 256, 32, 5, 2, 4, 2> Cfg;     // 8 waves of 128x64, ring of 5 x 32 k
-#elif MOE_GEMM_CFG == 3
-typedef TileCfg<256, 256, 64, 2, 2, 4, 2> Cfg;     // 8 waves of 128x64, ring of 2 x 64 k
-#elif MOE_GEMM_CFG == 4
-typedef TileCfg<256, 256, 32, 4, 2, 4, 2> Cfg;     // 8 waves of 128x64, ring of 4 x 32 k
-#elif MOE_GEMM_CFG == 5
-typedef TileCfg<256, 256, 32, 3, 2, 4, 2> Cfg;     // 8 waves of 128x64, ring of 3 x 32 k
+template <> struct CfgFor<EPI_GELU> { typedef Cfg8 type; };
+template <> struct CfgFor<EPI_DGELU> { typedef Cfg8 type; };
 #endif
+typedef CfgFor<EPI_DGELU>::type CfgDgelu;
 
-int gemm_bf16_dw_parts(int H) { return ((H + Cfg::BN - 1) / Cfg::BN) * Cfg::WAVES_N; }
+int gemm_bf16_dw_parts(int H) { return ((H + CfgDgelu::BN - 1) / CfgDgelu::BN) * CfgDgelu::WAVES_N; }
 
 template <int LAY, int EPI, typename C>
 static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
@@ -486,11 +574,11 @@ static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
 template <int LAY>
 static moe_status launch_lay(GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
     switch (epi) {
-        case EPI_STORE: return launch_one<LAY, EPI_STORE, Cfg>(a, s);
-        case EPI_GELU: return launch_one<LAY, EPI_GELU, Cfg>(a, s);
-        case EPI_DGELU: return launch_one<LAY, EPI_DGELU, Cfg>(a, s);
-        case EPI_ACCUM_F32: return launch_one<LAY, EPI_ACCUM_F32, Cfg>(a, s);
-        case EPI_STORE_F32: return launch_one<LAY, EPI_STORE_F32, Cfg>(a, s);
+        case EPI_STORE: return launch_one<LAY, EPI_STORE, typename CfgFor<EPI_STORE>::type>(a, s);
+        case EPI_GELU: return launch_one<LAY, EPI_GELU, typename CfgFor<EPI_GELU>::type>(a, s);
+        case EPI_DGELU: return launch_one<LAY, EPI_DGELU, typename CfgFor<EPI_DGELU>::type>(a, s);
+        case EPI_ACCUM_F32: return launch_one<LAY, EPI_ACCUM_F32, typename CfgFor<EPI_ACCUM_F32>::type>(a, s);
+        case EPI_STORE_F32: return launch_one<LAY, EPI_STORE_F32, typename CfgFor<EPI_STORE_F32>::type>(a, s);
     }
     return MOE_ERR_UNSUPPORTED;
 }
@@ -501,7 +589,8 @@ moe_status gemm_bf16(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStr
     if ((a.lda | a.ldb) & 7) return MOE_ERR_UNSUPPORTED;
     // buffer offsets are 32-bit: an expert's operand must stay below 2 GiB
     const long long ldmax = a.lda > a.ldb ? a.lda : a.ldb;
-    if (((long long)a.Cp + 8 * 64) * ldmax * 2 >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
+    const long long rmax = a.Cp > a.K ? a.Cp : a.K;
+    if ((rmax + 8 * 64) * ldmax * 2 >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
     if (lay == GEMM_NN) return launch_lay<GEMM_NN>(epi, a, s);
     if (lay == GEMM_NT) return launch_lay<GEMM_NT>(epi, a, s);
     return launch_lay<GEMM_TN>(epi, a, s);
