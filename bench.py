@@ -209,6 +209,41 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
     return out, shape, inp
 
 
+def granularity_report(args, shape, inp, reuse):
+    """Algorithm 1 (adaptive pipeline granularity) on this workload's layer at several batch
+    sizes: searches by timed trials where it must, answers from its range set where it can."""
+    import torch
+    from paper_2506_22175_amd import binding as B
+    from paper_2506_22175_amd import runner
+    cands = [1, 2, 4, 8]
+    full = shape.T
+    order = [full // 8, full // 4, full // 2, full, full * 3 // 8, full * 3 // 4]     # the last two fall between searched sizes
+    g = B.GranHandle()
+    rows = []
+    for T in order:
+        st = runner.LayerState(T, shape.M, shape.H, shape.E, shape.k, shape.capacity_factor, 1, shape.dtype, reuse,
+                               second_stream=not args.single_stream, size_for_partitions=cands)
+        st.upload({k_: (v[:T] if k_ in ("x", "dy") else v) for k_, v in inp.items()})
+        known = B.moe_gran_lookup(g, T)
+        row = {"T": T}
+        if known == -1:
+            best, ms = st.search_best_gran(cands, warmup=1, iters=3)
+            B.moe_gran_record(g, T, best)
+            row.update({"n": best, "how": "searched", "ms_per_step": dict(zip(map(str, cands), ms))})
+        else:
+            # answered from the range set; time the candidates anyway to check the answer
+            best, ms = st.search_best_gran(cands, warmup=1, iters=3)
+            row.update({"n": known, "how": "from range", "trial_best_n": best,
+                        "ms_per_step": dict(zip(map(str, cands), ms))})
+        rows.append(row)
+        del st
+        torch.cuda.empty_cache()
+    out = {"candidates": cands, "queries": rows,
+           "ranges": [{"lower": lo, "upper": up, "n": n} for lo, up, n in B.moe_gran_ranges(g)]}
+    g.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -238,6 +273,8 @@ def main():
             o, _, _ = measure(args, wl, n, 2, 5, 2, brief=True)
             others.append(o)
         out["other_workloads"] = others
+    if not args.no_sweep:
+        out["adaptive_granularity"] = granularity_report(args, shape, inp, args.reuse)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, inp, args.cpu_tokens)
     print(json.dumps(out))

@@ -219,6 +219,59 @@ const char* moe_status_string(moe_status s);
  * source line of the failing call); empty if there was none.  Host only. */
 const char* moe_last_error(void);
 
+/* ---- adaptive pipeline granularity (Algorithm 1, Section III-C) ------------------
+ * Which n a batch of B tokens should be cut into, with as few timed searches as
+ * possible: a table B -> n of answers given before, and the set S of pairs
+ * (range of B, n), one per n, which answers every B inside a known range on the
+ * hypothesis that the best n grows with B.  A handle owns both (host memory,
+ * created and destroyed by the caller; not thread-safe).
+ *
+ * moe_gran_lookup: the listing's first half.  *n = the cached n, else the n of the
+ *   range that holds B (then cached), else -1: a search is needed.  Should ranges
+ *   overlap (hypothesis violated), the one with the smallest lower bound wins.
+ * moe_gran_record: the listing's second half, after a search found n for B: the
+ *   pair of that n is inserted as range(B, B) or widened to hold B; B is cached.
+ * moe_gran_ranges: S ordered by lower bound; *count pairs (capacity 0: count only;
+ *   a smaller non-zero capacity is MOE_ERR_SHAPE).
+ * B <= 0 or n <= 0: MOE_ERR_SHAPE. */
+typedef struct moe_gran moe_gran;
+moe_status moe_gran_create(moe_gran** g);
+moe_status moe_gran_destroy(moe_gran* g);
+moe_status moe_gran_lookup(moe_gran* g, int64_t B, int32_t* n);
+moe_status moe_gran_record(moe_gran* g, int64_t B, int32_t n);
+moe_status moe_gran_ranges(const moe_gran* g, int32_t capacity, int64_t* lower, int64_t* upper,
+                           int32_t* n, int32_t* count);
+
+/* searchBestGran of Algorithm 1, by trials: for every candidate n (host array) runs
+ * `warmup` untimed and `iters` timed moe_layer_step calls on the given buffers with
+ * cfg->n_partitions replaced by the candidate (HIP events on streams[0]; blocks the
+ * host) and returns the candidate with the least time per step.  Candidates that
+ * do not divide T or whose workspace exceeds workspace_bytes are skipped.  counts
+ * must hold [max candidate, E].  Trials run with grad_overwrite forced on; outputs
+ * and gradients hold the last trial's results afterwards.
+ *   ms: time per step of each candidate in milliseconds, -1 for skipped; may be NULL.
+ *   No usable candidate: MOE_ERR_SHAPE. */
+moe_status moe_search_best_gran(const moe_config* cfg, const void* x, const void* dy,
+                                const void* Wg, const float* gate_bias, const void* W1, const void* W2,
+                                void* y, void* dx, float* dWg, float* dW1, float* dW2,
+                                float* logits, int32_t* topk_idx, float* topk_w, int32_t* slot, int32_t* counts,
+                                void* workspace, size_t workspace_bytes,
+                                void* const* streams, int32_t n_streams,
+                                const int32_t* candidates, int32_t n_candidates,
+                                int32_t warmup, int32_t iters, int32_t* best_n, float* ms);
+
+/* Algorithm 1 as a whole for B = cfg->T: lookup; if that fails, the search by
+ * trials above and the record.  *n is the answer, *searched (may be NULL) tells
+ * whether trials ran. */
+moe_status moe_gran_get(moe_gran* g, const moe_config* cfg, const void* x, const void* dy,
+                        const void* Wg, const float* gate_bias, const void* W1, const void* W2,
+                        void* y, void* dx, float* dWg, float* dW1, float* dW2,
+                        float* logits, int32_t* topk_idx, float* topk_w, int32_t* slot, int32_t* counts,
+                        void* workspace, size_t workspace_bytes,
+                        void* const* streams, int32_t n_streams,
+                        const int32_t* candidates, int32_t n_candidates,
+                        int32_t warmup, int32_t iters, int32_t* n, int32_t* searched);
+
 #ifdef __cplusplus
 }
 #endif

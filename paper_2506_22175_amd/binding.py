@@ -24,6 +24,8 @@ EXPORTS = [
     "moe_gate_bwd", "moe_gate_scratch_bytes", "moe_dispatch_bwd", "moe_layer_step",
     "moe_layer_forward", "moe_layer_backward", "moe_launch_counts", "moe_status_string",
     "moe_last_error", "moe_profile_enable", "moe_profile_read",
+    "moe_gran_create", "moe_gran_destroy", "moe_gran_lookup", "moe_gran_record", "moe_gran_ranges",
+    "moe_search_best_gran", "moe_gran_get",
 ]
 
 
@@ -227,3 +229,78 @@ def moe_layer_backward(cfg, x, dy, Wg, W1, W2, dx, dWg, dW1, dW2, logits, topk_i
                                     _p(dW2), _p(logits), _p(topk_idx), _p(topk_w), _p(slot), _p(counts),
                                     _p(workspace), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
                                     arr, n), "moe_layer_backward")
+
+
+# ---- adaptive pipeline granularity ---------------------------------------------------
+
+class GranHandle:
+    """Owner of a moe_gran handle (the table and the range set of the granularity search)."""
+
+    def __init__(self):
+        self._h = ctypes.c_void_p(0)
+        _check(lib().moe_gran_create(ctypes.byref(self._h)), "moe_gran_create")
+
+    def close(self):
+        if self._h:
+            lib().moe_gran_destroy(self._h)
+            self._h = ctypes.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def moe_gran_lookup(g: GranHandle, B: int) -> int:
+    n = ctypes.c_int32(0)
+    _check(lib().moe_gran_lookup(g._h, ctypes.c_int64(B), ctypes.byref(n)), "moe_gran_lookup")
+    return n.value
+
+
+def moe_gran_record(g: GranHandle, B: int, n: int):
+    _check(lib().moe_gran_record(g._h, ctypes.c_int64(B), ctypes.c_int32(n)), "moe_gran_record")
+
+
+def moe_gran_ranges(g: GranHandle):
+    """[(lower, upper, n), ...] ordered by lower bound."""
+    count = ctypes.c_int32(0)
+    _check(lib().moe_gran_ranges(g._h, ctypes.c_int32(0), None, None, None, ctypes.byref(count)), "moe_gran_ranges")
+    c = count.value
+    lo, up, nn = (ctypes.c_int64 * max(c, 1))(), (ctypes.c_int64 * max(c, 1))(), (ctypes.c_int32 * max(c, 1))()
+    _check(lib().moe_gran_ranges(g._h, ctypes.c_int32(c), lo, up, nn, ctypes.byref(count)), "moe_gran_ranges")
+    return [(int(lo[i]), int(up[i]), int(nn[i])) for i in range(c)]
+
+
+def _layer_args(cfg, x, dy, Wg, gate_bias, W1, W2, y, dx, dWg, dW1, dW2, logits, topk_idx, topk_w, slot, counts,
+                workspace, streams):
+    arr, n = _streams(streams)
+    return (_cfg(cfg), _p(x), _p(dy), _p(Wg), _p(gate_bias), _p(W1), _p(W2), _p(y), _p(dx), _p(dWg), _p(dW1),
+            _p(dW2), _p(logits), _p(topk_idx), _p(topk_w), _p(slot), _p(counts), _p(workspace),
+            ctypes.c_size_t(workspace.numel() * workspace.element_size()), arr, n), arr
+
+
+def moe_search_best_gran(cfg, x, dy, Wg, gate_bias, W1, W2, y, dx, dWg, dW1, dW2, logits, topk_idx, topk_w, slot,
+                         counts, workspace, streams, candidates, warmup=1, iters=3):
+    """(best n, [ms per step per candidate, -1 = skipped])."""
+    args, keep = _layer_args(cfg, x, dy, Wg, gate_bias, W1, W2, y, dx, dWg, dW1, dW2, logits, topk_idx, topk_w,
+                             slot, counts, workspace, streams)
+    cand = (ctypes.c_int32 * len(candidates))(*candidates)
+    ms = (ctypes.c_float * len(candidates))()
+    best = ctypes.c_int32(0)
+    _check(lib().moe_search_best_gran(*args, cand, ctypes.c_int32(len(candidates)), ctypes.c_int32(warmup),
+                                      ctypes.c_int32(iters), ctypes.byref(best), ms), "moe_search_best_gran")
+    return best.value, [float(v) for v in ms]
+
+
+def moe_gran_get(g: GranHandle, cfg, x, dy, Wg, gate_bias, W1, W2, y, dx, dWg, dW1, dW2, logits, topk_idx, topk_w,
+                 slot, counts, workspace, streams, candidates, warmup=1, iters=3):
+    """(n, searched) for B = cfg.T."""
+    args, keep = _layer_args(cfg, x, dy, Wg, gate_bias, W1, W2, y, dx, dWg, dW1, dW2, logits, topk_idx, topk_w,
+                             slot, counts, workspace, streams)
+    cand = (ctypes.c_int32 * len(candidates))(*candidates)
+    n = ctypes.c_int32(0)
+    searched = ctypes.c_int32(0)
+    _check(lib().moe_gran_get(g._h, *args, cand, ctypes.c_int32(len(candidates)), ctypes.c_int32(warmup),
+                              ctypes.c_int32(iters), ctypes.byref(n), ctypes.byref(searched)), "moe_gran_get")
+    return n.value, bool(searched.value)

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmoe_hip.so")
 SOURCES = ["core.hip", "route.hip", "slots.hip", "permute.hip", "gemm_f32.hip", "gemm_bf16.hip",
-           "ffn.hip", "layer.hip"]
+           "ffn.hip", "layer.hip", "gran.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
          "-I", CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -29,12 +29,18 @@ class LayerState:
     """All device buffers of one layer step for a given configuration."""
 
     def __init__(self, T, M, H, E, k, capacity_factor, n_partitions=1, dtype="bf16", reuse=0, device="cuda:0",
-                 second_stream: bool = True, grad_overwrite: int = 0):
+                 second_stream: bool = True, grad_overwrite: int = 0, size_for_partitions=()):
         self.dtype = dtype
         self.device = device
         self.cfg = B.make_config(T, M, H, E, k, capacity_factor, n_partitions, _MOE_DT[dtype], reuse, grad_overwrite)
         self.C_p = B.moe_capacity(self.cfg)
         self.ws_total, self.ws_saved, self.ws_temp, self.ws_routing = B.moe_workspace_bytes(self.cfg)
+        ws_alloc, n_max = self.ws_total, n_partitions
+        for n_alt in size_for_partitions:      # buffers that also fit these partition counts (granularity search)
+            if T % n_alt == 0:
+                alt = B.make_config(T, M, H, E, k, capacity_factor, n_alt, _MOE_DT[dtype], reuse, grad_overwrite)
+                ws_alloc = max(ws_alloc, B.moe_workspace_bytes(alt)[0])
+                n_max = max(n_max, n_alt)
         td = _TORCH_DT[dtype]
         dev = device
         self.y = torch.empty((T, M), dtype=td, device=dev)
@@ -46,8 +52,8 @@ class LayerState:
         self.topk_idx = torch.empty((T, k), dtype=torch.int32, device=dev)
         self.topk_w = torch.empty((T, k), dtype=torch.float32, device=dev)
         self.slot = torch.empty((T, k), dtype=torch.int32, device=dev)
-        self.counts = torch.empty((n_partitions, E), dtype=torch.int32, device=dev)
-        self.workspace = torch.empty((self.ws_total,), dtype=torch.uint8, device=dev)
+        self.counts = torch.empty((n_max, E), dtype=torch.int32, device=dev)
+        self.workspace = torch.empty((ws_alloc,), dtype=torch.uint8, device=dev)
         self.s0 = torch.cuda.current_stream(dev)
         self.s1 = torch.cuda.Stream(dev) if second_stream else self.s0
         self.inputs: Dict[str, Optional[torch.Tensor]] = {}
@@ -88,6 +94,22 @@ class LayerState:
         B.moe_layer_backward(self.cfg, i["x"], i["dy"], i["Wg"], i["W1"], i["W2"], self.dx, self.dWg, self.dW1,
                              self.dW2, self.logits, self.topk_idx, self.topk_w, self.slot, self.counts,
                              self.workspace, [self.s0, self.s1])
+
+    def search_best_gran(self, candidates, warmup=1, iters=3):
+        """Timed trials of the step over the candidate partition counts (this state's buffers
+        must have been sized for the largest candidate).  Returns (best n, ms per candidate)."""
+        i = self.inputs
+        return B.moe_search_best_gran(self.cfg, i["x"], i["dy"], i["Wg"], i["gate_bias"], i["W1"], i["W2"], self.y,
+                                      self.dx, self.dWg, self.dW1, self.dW2, self.logits, self.topk_idx,
+                                      self.topk_w, self.slot, self.counts, self.workspace, [self.s0, self.s1],
+                                      candidates, warmup, iters)
+
+    def gran_get(self, handle, candidates, warmup=1, iters=3):
+        """Algorithm 1 for this state's batch size: (n, searched)."""
+        i = self.inputs
+        return B.moe_gran_get(handle, self.cfg, i["x"], i["dy"], i["Wg"], i["gate_bias"], i["W1"], i["W2"], self.y,
+                              self.dx, self.dWg, self.dW1, self.dW2, self.logits, self.topk_idx, self.topk_w,
+                              self.slot, self.counts, self.workspace, [self.s0, self.s1], candidates, warmup, iters)
 
     def capture(self):
         """Record one step into a HIP graph (all launches and the cross-stream events of

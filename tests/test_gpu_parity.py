@@ -358,3 +358,30 @@ def test_graph_replay_equals_eager_every_time(runner):
         st.zero_grads()
         st.step()                      # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_granularity_search_by_trials_and_algorithm_one_on_the_gpu(oracle, runner):
+    """searchBestGran (Algorithm 1, Section III-C) times the real step for each candidate n;
+    the whole algorithm then answers a repeated batch size from its table, and a step with the
+    chosen n matches the oracle like any other."""
+    from paper_2506_22175_amd import binding as B
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=4)
+    cands = [1, 2, 3, 4, 8]                                  # 3 does not divide T: skipped
+    st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, 1, s.dtype, 2, size_for_partitions=cands)
+    st.upload(d)
+    st.poison()
+    best, ms = st.search_best_gran(cands, warmup=1, iters=3)
+    assert ms[2] == -1.0 and all(m > 0 for i, m in enumerate(ms) if i != 2)
+    assert best == cands[min((m, i) for i, m in enumerate(ms) if m > 0)[1]]
+    g = B.GranHandle()
+    n1, searched1 = st.gran_get(g, cands)
+    n2, searched2 = st.gran_get(g, cands)
+    assert searched1 and not searched2 and n1 == n2 and n1 in (1, 2, 4, 8)
+    assert B.moe_gran_ranges(g) == [(s.T, s.T, n1)]
+    g.close()
+    # the chosen n is an ordinary configuration: parity as usual
+    r = _oracle(oracle, s, d, n1)
+    out = runner.run_layer_step(s, d, n1, 2)
+    _check_routing(out, r)
+    _check_values(out, r, TOL[s.dtype])
