@@ -156,6 +156,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
 
     # the same kernels with the schedule serialised on one stream (no GEMM running beside them)
     hbm_alone = {}
+    others_alone = {}
     if not brief and not args.single_stream:
         keep = st.s1
         st.s1 = st.s0
@@ -172,6 +173,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
             if l and ms > 0:
                 gbs = nbytes * per_step * 3 / (ms * 1e-3) / 1e9
                 hbm_alone[name] = {"avg_us": 1e3 * ms / l, "GB/s": gbs, "frac": gbs / PEAK_HBM_GBS}
+        others_alone = {kd: prof1[kd][1] / 3 for kd in ("route", "slots", "gate_bwd")}
 
     mem = {}
     for mode in (0, 1, 2):
@@ -196,6 +198,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
         "tflops_executed": flop_exec / (ms_per_step * 1e-3) / 1e12,
         "roofline": roofline, "hbm_kernels": hbm, "hbm_kernels_alone": hbm_alone, "memory_bytes": mem,
         "other_kernels_ms_per_step": {kd: prof[kd][1] / steps for kd in ("route", "slots", "gate_bwd")},
+        "other_kernels_alone_ms_per_step": others_alone,
         "paper_context": "MPipeMoE reports up to 2.8x speedup and up to 47% less memory than FasterMoE on 64 A100 "
                          "GPUs (8 DGX A100); ratios on other hardware, not a target for this number",
     }

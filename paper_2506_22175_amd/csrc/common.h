@@ -66,6 +66,35 @@ template <> struct Vec8<float> {
     }
 };
 
+// Eight consecutive elements as they come from memory; converted when used, so that a
+// loop can request the next ones before it works on the current ones.
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> {
+    uint4 u;
+    __device__ __forceinline__ void load(const bf16_t* p) { u = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void zero() { u = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void to_float(float* o) const {
+        const unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o[2 * i] = __uint_as_float(w[i] << 16);
+            o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+template <> struct Raw8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const float* p) {
+        a = *reinterpret_cast<const float4*>(p);
+        b = *reinterpret_cast<const float4*>(p + 4);
+    }
+    __device__ __forceinline__ void zero() { a = make_float4(0, 0, 0, 0); b = a; }
+    __device__ __forceinline__ void to_float(float* o) const {
+        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+        o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+    }
+};
+
 // GeLU in its erf form, z * Phi(z), and its derivative Phi(z) + z * phi(z).
 // erf is evaluated with the five-term rational approximation of Abramowitz &
 // Stegun 7.1.26 (absolute error below 1.5e-7, far inside the float32 tolerance),

@@ -215,6 +215,99 @@ __global__ __launch_bounds__(DXL_THREADS) void dispatch_bwd_lds_kernel(
     }
 }
 
+// The same with the gate matrix in LDS as float (no conversion per token) and two tokens per
+// wavefront at a time (each LDS read feeds two tokens).  Row e of W_g^T is stored so that the
+// 16 bytes a lane reads are contiguous across lanes: element d = unit*N + 4*h + r sits at
+// e*M + h*(M/N)*4 + unit*4 + r (N = elements of the storage type per 16-byte unit).
+constexpr int DXF_THREADS = 1024;
+constexpr int DXF_WAVES = DXF_THREADS / 64;
+template <typename T>
+__global__ __launch_bounds__(DXF_THREADS) void dispatch_bwd_f32lds_kernel(
+    const T* __restrict__ dDI, const int* __restrict__ slot, const float* __restrict__ dL,
+    const T* __restrict__ Wg, T* __restrict__ dx, int t_begin, int t_count, int M, int E, int k) {
+    extern __shared__ __attribute__((aligned(16))) char dxb_smem[];
+    float* wgt = reinterpret_cast<float*>(dxb_smem);
+    constexpr int N = Unit<T>::N;
+    constexpr int NH = N / 4;
+    const int U = M / N;
+#pragma unroll 8
+    for (int q = threadIdx.x; q < M * E; q += DXF_THREADS) {
+        const int e = q / M, d = q - e * M;
+        const int unit = d / N, h = (d % N) >> 2, r = d & 3;
+        wgt[e * M + h * U * 4 + unit * 4 + r] = Elem<T>::ld(Wg + (size_t)d * E + e);
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    for (int tl = 2 * (blockIdx.x * DXF_WAVES + wid); tl < t_count; tl += 2 * gridDim.x * DXF_WAVES) {
+        const int ntok = min(2, t_count - tl);
+        for (int c0 = 0; c0 < U; c0 += 256) {
+            float acc[2][4][N];
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int i = 0; i < N; ++i) acc[a][u][i] = 0.0f;
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                if (a >= ntok) continue;
+                const int t = t_begin + tl + a;
+                for (int j = 0; j < k; ++j) {
+                    const int sj = slot[(size_t)t * k + j];
+                    if (sj < 0) continue;
+                    const uint4* in = reinterpret_cast<const uint4*>(dDI + (size_t)sj * M);
+                    uint4 v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int c = c0 + u * 64 + lane;
+                        v[u] = c < U ? in[c] : make_uint4(0, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        float r[N];
+                        Unit<T>::to_float(v[u], r);
+#pragma unroll
+                        for (int i = 0; i < N; ++i) acc[a][u][i] += r[i];
+                    }
+                }
+            }
+            const float* g0 = dL + (size_t)(t_begin + tl) * E;
+            const float* g1 = dL + (size_t)(t_begin + tl + ntok - 1) * E;     // the same token again when only one is left
+            for (int e = 0; e < E; ++e) {
+                const float ge0 = g0[e], ge1 = g1[e];
+                const float* wrow = wgt + (size_t)e * M;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + u * 64 + lane;
+                    if (c < U) {
+#pragma unroll
+                        for (int h = 0; h < NH; ++h) {
+                            const float4 w4 = *reinterpret_cast<const float4*>(wrow + h * U * 4 + c * 4);
+                            const float w[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                acc[0][u][4 * h + r] = fmaf(ge0, w[r], acc[0][u][4 * h + r]);
+                                acc[1][u][4 * h + r] = fmaf(ge1, w[r], acc[1][u][4 * h + r]);
+                            }
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                if (a >= ntok) continue;
+                uint4* out = reinterpret_cast<uint4*>(dx + (size_t)(t_begin + tl + a) * M);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + u * 64 + lane;
+                    if (c < U) out[c] = Unit<T>::from_float(acc[a][u]);
+                }
+            }
+        }
+    }
+}
+
 // dx[t] = sum_j dDI[slot[t,j]] + dL[t,:] Wg^T.  A thread owns eight columns and
 // keeps their gate weights in registers across TOKB tokens.
 constexpr int DXB_TOK = 32;
@@ -317,7 +410,10 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
     const T* __restrict__ x, const float* __restrict__ logits, const int* __restrict__ topk_idx,
     const int* __restrict__ slot, const float* __restrict__ dw, const float* __restrict__ dw_part, int parts,
     float* __restrict__ dL, float* __restrict__ part, int t_begin, int t_count, int M, int E, int k) {
-    __shared__ float sdl[DWG_TOK][DWG_EMAX + 1];
+    // dL of the block's tokens; rows of missing tokens and columns from E up to the next
+    // multiple of 16 stay zero, so the product loop below needs no predicates
+    __shared__ __attribute__((aligned(16))) float sdl[DWG_TOK][DWG_EMAX + 4];
+    for (int q = threadIdx.x; q < DWG_TOK * (DWG_EMAX + 4); q += PERM_THREADS) (&sdl[0][0])[q] = 0.0f;
     const int tl0 = blockIdx.y * DWG_TOK;
     const int nt = min(DWG_TOK, t_count - tl0);
     // combine-weight gradients of the block's (token, choice) pairs: either given, or the
@@ -331,9 +427,25 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
         if (dw_part) {
             const int sl = slot[(size_t)t * k + j];
             if (sl >= 0) {
-                const int per = (parts + 3) >> 2;
-                const int c1 = min(parts, (sub + 1) * per);
-                for (int c = sub * per; c < c1; ++c) v += dw_part[(size_t)sl * parts + c];
+                const float* row = dw_part + (size_t)sl * parts;
+                if ((parts & 3) == 0) {
+                    // lane `sub` of the pair takes every fourth group of four partial sums, all
+                    // requested before the first is added (fixed order: groups ascending, then the lanes)
+                    const int ngrp = parts >> 2;
+                    for (int g0 = sub; g0 < ngrp; g0 += 32) {
+                        float4 q4[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            q4[u] = (g0 + 4 * u < ngrp) ? *reinterpret_cast<const float4*>(row + 4 * (g0 + 4 * u))
+                                                        : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) v += (q4[u].x + q4[u].y) + (q4[u].z + q4[u].w);
+                    }
+                } else {
+                    const int per = (parts + 3) >> 2;
+                    const int c1 = min(parts, (sub + 1) * per);
+                    for (int c = sub * per; c < c1; ++c) v += row[c];
+                }
             }
         } else if (sub == 0) {
             v = dw[(size_t)t * k + j];
@@ -354,32 +466,51 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
             for (int i = 0; i < 8; ++i)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
+            // the rows of the next four tokens are requested before the current four are used
+            // (tokens past the end are clamped here and get weight zero below)
+            Raw8<T> cur[4], nxt[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cur[u].load(x + (size_t)(t_begin + tl0 + min(u, nt - 1)) * M + c);
             for (int i0 = 0; i0 < nt; i0 += 4) {
+                if (i0 + 4 < nt) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) nxt[u].load(x + (size_t)(t_begin + tl0 + min(i0 + 4 + u, nt - 1)) * M + c);
+                }
                 float xv[4][8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (i0 + u < nt) Vec8<T>::load(x + (size_t)(t_begin + tl0 + i0 + u) * M + c, xv[u]);
-                    else {
+                for (int u = 0; u < 4; ++u) cur[u].to_float(xv[u]);
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) xv[u][q] = 0.0f;
+                for (int u = 0; u < 4; ++u) {
+                    float4 g4[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) g4[v] = *reinterpret_cast<const float4*>(&sdl[i0 + u][e0 + 4 * v]);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float gd[4] = {g4[v].x, g4[v].y, g4[v].z, g4[v].w};
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+#pragma unroll
+                            for (int q = 0; q < 8; ++q) acc[q][4 * v + r] = fmaf(xv[u][q], gd[r], acc[q][4 * v + r]);
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const float gd = (e < ne && i0 + u < nt) ? sdl[i0 + u][e0 + e] : 0.0f;
-#pragma unroll
-                        for (int q = 0; q < 8; ++q) acc[q][e] = fmaf(xv[u][q], gd, acc[q][e]);
-                    }
-                }
+                for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
             }
             float* out = part + ((size_t)blockIdx.y * M + c) * E + e0;
+            if (ne == 16 && (E & 3) == 0) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q)
+                for (int q = 0; q < 8; ++q)
 #pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    if (e < ne) out[(size_t)q * E + e] = acc[q][e];
+                    for (int v = 0; v < 4; ++v)
+                        *reinterpret_cast<float4*>(out + (size_t)q * E + 4 * v) =
+                            make_float4(acc[q][4 * v], acc[q][4 * v + 1], acc[q][4 * v + 2], acc[q][4 * v + 3]);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (e < ne) out[(size_t)q * E + e] = acc[q][e];
+            }
         }
     }
 }
@@ -424,6 +555,21 @@ template <typename T>
 static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const int* slot, const float* dL,
                                  const void* Wg, void* dx, hipStream_t s) {
     const size_t wg_bytes = (size_t)d.M * d.E * sizeof(T);
+    const size_t wg_float_bytes = (size_t)d.M * d.E * sizeof(float);
+    if (wg_float_bytes <= 128 * 1024) {
+        auto kern = dispatch_bwd_f32lds_kernel<T>;
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)wg_float_bytes));
+        int blocks = (d.Tp + 2 * DXF_WAVES - 1) / (2 * DXF_WAVES);
+        const int cap = wg_float_bytes > 64 * 1024 ? 256 : 512;      // workgroups that fit the chip at once
+        if (blocks > cap) blocks = cap;
+        ProfScope ps(PK_DISPATCH_BWD, s);
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(DXF_THREADS), wg_float_bytes, s, (const T*)dDI, slot, dL,
+                           (const T*)Wg, (T*)dx, part * d.Tp, d.Tp, d.M, d.E, d.k);
+        count_launch(LC_PERMUTE);
+        MOE_CHECK_LAUNCH();
+        return MOE_OK;
+    }
     if (wg_bytes <= 64 * 1024) {
         auto kern = dispatch_bwd_lds_kernel<T>;
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -91,29 +91,51 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
                 __syncthreads();
                 // LDS element of (row dl, expert e): span = dl/512, lane l = (dl/8)%64, i = dl%8
                 //   index = ((((span*8 + i) * E4 + e/4) * 64 + l) * 4 + e%4
-                for (int q = tid; q < MC * EP; q += ROUTE_THREADS) {
-                    int dl = q / EP, e = q % EP;
-                    int d = c0 + dl;
-                    float v = 0.0f;
-                    if (d < M && e < E) v = Elem<T>::ld(Wg + (size_t)d * E + e);
-                    int span = dl >> 9, l = (dl >> 3) & 63, i = dl & 7;
-                    wl[((((span * 8 + i) * E4 + (e >> 2)) * 64 + l) << 2) + (e & 3)] = v;
+                if (EP % 8 == 0 && E == EP && (reinterpret_cast<unsigned long long>(Wg) & 15ull) == 0) {
+                    // eight experts of one row per load, several loads in flight per thread
+                    constexpr int G = EP / 8 > 0 ? EP / 8 : 1;
+#pragma unroll 4
+                    for (int q = tid; q < MC * G; q += ROUTE_THREADS) {
+                        const int dl = q / G, e0 = (q % G) * 8;
+                        const int d = c0 + dl;
+                        float v[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+                        if (d < M) Vec8<T>::load(Wg + (size_t)d * E + e0, v);
+                        const int span = dl >> 9, l = (dl >> 3) & 63, i = dl & 7;
+                        float* dst = wl + ((((span * 8 + i) * E4 + (e0 >> 2)) * 64 + l) << 2);
+                        *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                        *reinterpret_cast<float4*>(dst + 256) = make_float4(v[4], v[5], v[6], v[7]);
+                    }
+                } else {
+                    for (int q = tid; q < MC * EP; q += ROUTE_THREADS) {
+                        int dl = q / EP, e = q % EP;
+                        int d = c0 + dl;
+                        float v = 0.0f;
+                        if (d < M && e < E) v = Elem<T>::ld(Wg + (size_t)d * E + e);
+                        int span = dl >> 9, l = (dl >> 3) & 63, i = dl & 7;
+                        wl[((((span * 8 + i) * E4 + (e >> 2)) * 64 + l) << 2) + (e & 3)] = v;
+                    }
                 }
                 __syncthreads();
             }
             const int nspan = (min(MC, M - c0) + 511) / 512;
+            // token elements of the next span are requested before the current span is multiplied
+            Raw8<T> xr[TB], xn[TB];
+            auto fetch = [&](int sp, Raw8<T>* r) {
+                const int d0 = c0 + sp * 512 + lane * 8;
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) {
+                    if (d0 < M && t0 + tb < Ttot) r[tb].load(x + (size_t)(t0 + tb) * M + d0);
+                    else r[tb].zero();
+                }
+            };
+            fetch(0, xr);
             for (int sp = 0; sp < nspan; ++sp) {
                 const int d0 = c0 + sp * 512 + lane * 8;
+                if (sp + 1 < nspan) fetch(sp + 1, xn);
                 if (d0 < M) {
                     float xs[TB][8];
 #pragma unroll
-                    for (int tb = 0; tb < TB; ++tb) {
-                        if (t0 + tb < Ttot) Vec8<T>::load(x + (size_t)(t0 + tb) * M + d0, xs[tb]);
-                        else {
-#pragma unroll
-                            for (int i = 0; i < 8; ++i) xs[tb][i] = 0.0f;
-                        }
-                    }
+                    for (int tb = 0; tb < TB; ++tb) xr[tb].to_float(xs[tb]);
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
 #pragma unroll
@@ -131,6 +153,8 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
                         }
                     }
                 }
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) xr[tb] = xn[tb];
             }
         }
 
