@@ -142,81 +142,9 @@ __global__ __launch_bounds__(PERM_THREADS) void combine_kernel(
     }
 }
 
-// dx[t] = sum_j dDI[slot[t,j]] + dL[t,:] Wg^T with the gate matrix transposed into LDS
-// ([E][M] in the storage type).  One wavefront per token, workgroups walk over tokens.
-constexpr int DXL_THREADS = 512;
-constexpr int DXL_WAVES = DXL_THREADS / 64;
-template <typename T>
-__global__ __launch_bounds__(DXL_THREADS) void dispatch_bwd_lds_kernel(
-    const T* __restrict__ dDI, const int* __restrict__ slot, const float* __restrict__ dL,
-    const T* __restrict__ Wg, T* __restrict__ dx, int t_begin, int t_count, int M, int E, int k) {
-    extern __shared__ __attribute__((aligned(16))) char dxb_smem[];
-    T* wgt = reinterpret_cast<T*>(dxb_smem);                 // wgt[e*M + d]
-    // consecutive lanes take consecutive d of one e: conflict-free LDS writes (the strided
-    // global reads come from L2, the matrix is small)
-    for (int q = threadIdx.x; q < M * E; q += DXL_THREADS) {
-        const int e = q / M, d = q - e * M;
-        wgt[q] = Wg[(size_t)d * E + e];
-    }
-    __syncthreads();
-    const int lane = threadIdx.x & 63;
-    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    constexpr int N = Unit<T>::N;
-    const int U = M / N;
-    for (int tl = blockIdx.x * DXL_WAVES + wid; tl < t_count; tl += gridDim.x * DXL_WAVES) {
-        const int t = t_begin + tl;
-        int s[8];
-        for (int j = 0; j < k; ++j) s[j] = slot[(size_t)t * k + j];
-        const float* g = dL + (size_t)t * E;
-        uint4* out = reinterpret_cast<uint4*>(dx + (size_t)t * M);
-        for (int c0 = 0; c0 < U; c0 += 256) {
-            float acc[4][N];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int i = 0; i < N; ++i) acc[u][i] = 0.0f;
-            for (int j = 0; j < k; ++j) {
-                if (s[j] < 0) continue;
-                const uint4* in = reinterpret_cast<const uint4*>(dDI + (size_t)s[j] * M);
-                uint4 v[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int c = c0 + u * 64 + lane;
-                    v[u] = c < U ? in[c] : make_uint4(0, 0, 0, 0);
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    float r[N];
-                    Unit<T>::to_float(v[u], r);
-#pragma unroll
-                    for (int i = 0; i < N; ++i) acc[u][i] += r[i];
-                }
-            }
-            for (int e = 0; e < E; ++e) {
-                const float ge = g[e];
-                const uint4* wrow = reinterpret_cast<const uint4*>(wgt + (size_t)e * M);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int c = c0 + u * 64 + lane;
-                    if (c < U) {
-                        float r[N];
-                        Unit<T>::to_float(wrow[c], r);
-#pragma unroll
-                        for (int i = 0; i < N; ++i) acc[u][i] = fmaf(ge, r[i], acc[u][i]);
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int c = c0 + u * 64 + lane;
-                if (c < U) out[c] = Unit<T>::from_float(acc[u]);
-            }
-        }
-    }
-}
-
-// The same with the gate matrix in LDS as float (no conversion per token) and two tokens per
-// wavefront at a time (each LDS read feeds two tokens).  Row e of W_g^T is stored so that the
+// dx[t] = sum_j dDI[slot[t,j]] + dL[t,:] Wg^T with the gate matrix transposed into LDS as
+// float (no conversion per token); a wavefront takes two tokens at a time, so each LDS read
+// feeds two tokens, and workgroups walk over the tokens.  Row e of W_g^T is stored so that the
 // 16 bytes a lane reads are contiguous across lanes: element d = unit*N + 4*h + r sits at
 // e*M + h*(M/N)*4 + unit*4 + r (N = elements of the storage type per 16-byte unit).
 constexpr int DXF_THREADS = 1024;
@@ -554,7 +482,6 @@ static moe_status dispatch_t(const Dims& d, int part, const void* src, const int
 template <typename T>
 static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const int* slot, const float* dL,
                                  const void* Wg, void* dx, hipStream_t s) {
-    const size_t wg_bytes = (size_t)d.M * d.E * sizeof(T);
     const size_t wg_float_bytes = (size_t)d.M * d.E * sizeof(float);
     if (wg_float_bytes <= 128 * 1024) {
         auto kern = dispatch_bwd_f32lds_kernel<T>;
@@ -565,19 +492,6 @@ static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const
         if (blocks > cap) blocks = cap;
         ProfScope ps(PK_DISPATCH_BWD, s);
         hipLaunchKernelGGL(kern, dim3(blocks), dim3(DXF_THREADS), wg_float_bytes, s, (const T*)dDI, slot, dL,
-                           (const T*)Wg, (T*)dx, part * d.Tp, d.Tp, d.M, d.E, d.k);
-        count_launch(LC_PERMUTE);
-        MOE_CHECK_LAUNCH();
-        return MOE_OK;
-    }
-    if (wg_bytes <= 64 * 1024) {
-        auto kern = dispatch_bwd_lds_kernel<T>;
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)wg_bytes));
-        int blocks = (d.Tp + DXL_WAVES - 1) / DXL_WAVES;
-        if (blocks > 512) blocks = 512;          // two workgroups fit on a CU; each walks over its tokens
-        ProfScope ps(PK_DISPATCH_BWD, s);
-        hipLaunchKernelGGL(kern, dim3(blocks), dim3(DXL_THREADS), wg_bytes, s, (const T*)dDI, slot, dL,
                            (const T*)Wg, (T*)dx, part * d.Tp, d.Tp, d.M, d.E, d.k);
         count_launch(LC_PERMUTE);
         MOE_CHECK_LAUNCH();

@@ -98,6 +98,9 @@ CASES = [
     ("min_dims_bf16", 24, 8, 8, 3, 2, 1.0, "bf16", 3, None),
     ("one_token_per_partition", 4, 64, 64, 4, 2, 2.0, "f32", 4, None),
     ("wide_bf16", 512, 1536, 640, 8, 2, 1.25, "bf16", 2, None),
+    # gate matrix too large for LDS: streamed in pieces by the gate, register-held in dispatch backward
+    ("big_gate_bf16", 256, 2560, 64, 32, 2, 1.0, "bf16", 2, None),
+    ("big_gate_f32", 128, 1088, 32, 33, 3, 1.0, "f32", 1, None),
 ]
 
 
