@@ -157,6 +157,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
     # the same kernels with the schedule serialised on one stream (no GEMM running beside them)
     hbm_alone = {}
     others_alone = {}
+    cost_model = {}
     if not brief and not args.single_stream:
         keep = st.s1
         st.s1 = st.s0
@@ -174,6 +175,29 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
                 gbs = nbytes * per_step * 3 / (ms * 1e-3) / 1e9
                 hbm_alone[name] = {"avg_us": 1e3 * ms / l, "GB/s": gbs, "frac": gbs / PEAK_HBM_GBS}
         others_alone = {kd: prof1[kd][1] / 3 for kd in ("route", "slots", "gate_bwd")}
+        # interference and the strategy cost model (Sections II-C, III-E): speeds alone, relative speeds
+        # when GEMMs and permutations run side by side, Eq. 10 per micro-batch against the measured step
+        g_alone_ms = sum(prof1[kd][1] for kd in GEMM_KINDS) / 3
+        perm_corun_ms = (prof["dispatch"][1] + prof["combine"][1]) / steps
+        perm_alone_ms = (prof1["dispatch"][1] + prof1["combine"][1]) / 3
+        if g_alone_ms > 0 and perm_alone_ms > 0 and perm_corun_ms > 0:
+            rows_pp = R / n                                              # kept rows of a micro-batch
+            exchanges = (n_disp_per_step + 1) * n                        # dispatch and combine launches per step
+            sp = B.MoESpeeds(W_comp=g_flop_per_step / 2.0 / (g_alone_ms * 1e-3),
+                             W_comm=exchanges * rows_pp * M / (perm_alone_ms * 1e-3), W_mem=1.0,
+                             sigma=min(1.0, g_alone_ms / (g_ms / steps)), mu_comp=min(1.0, perm_alone_ms / perm_corun_ms),
+                             mu_all=1.0, eta_all=1.0)
+            model = {}
+            for name, num in (("none", 0), ("S4", 4)):
+                fw, bw = B.moe_strategy_cost(num, int(round(rows_pp)), M, H, sp)
+                model[name] = {"fw_ms_per_microbatch": fw * 1e3, "bw_ms_per_microbatch": bw * 1e3,
+                               "step_ms": n * (fw + bw) * 1e3}
+            pick, _ = B.moe_select_strategy(0b10001, int(round(rows_pp)), M, H, sp)
+            cost_model = {"W_comp_TMAC_per_s": sp.W_comp / 1e12, "W_comm_Gelem_per_s": sp.W_comm / 1e9,
+                          "sigma_comp_beside_permutations": sp.sigma, "mu_permutations_beside_comp": sp.mu_comp,
+                          "eq10": model, "cheapest_of_none_and_S4": B.STRATEGIES[pick],
+                          "this_run": {"strategy": {0: "none", 2: "S4"}.get(reuse, "mode 1 (no row in Table II)"),
+                                       "measured_step_ms": ms_per_step}}
 
     mem = {}
     for mode in (0, 1, 2):
@@ -199,6 +223,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
         "roofline": roofline, "hbm_kernels": hbm, "hbm_kernels_alone": hbm_alone, "memory_bytes": mem,
         "other_kernels_ms_per_step": {kd: prof[kd][1] / steps for kd in ("route", "slots", "gate_bwd")},
         "other_kernels_alone_ms_per_step": others_alone,
+        "interference_and_cost_model": cost_model,
         "paper_context": "MPipeMoE reports up to 2.8x speedup and up to 47% less memory than FasterMoE on 64 A100 "
                          "GPUs (8 DGX A100); ratios on other hardware, not a target for this number",
     }
@@ -270,10 +295,11 @@ def main():
     if not args.no_sweep:
         # the other workloads of the set, a few steps each, for the record
         others = []
-        for wl, n in (("small", 1), ("gpt", 1), ("gpt", 4), ("skewed", 4), ("large", 4), ("large", 8)):
-            if wl == args.workload and n == args.n:
+        for wl, n, mode in (("small", 1, 2), ("gpt", 1, 2), ("gpt", 4, 2), ("skewed", 4, 2), ("large", 4, 2),
+                            ("large", 8, 2), (args.workload, args.n, 0), (args.workload, args.n, 1)):
+            if wl == args.workload and n == args.n and mode == args.reuse:
                 continue
-            o, _, _ = measure(args, wl, n, 2, 5, 2, brief=True)
+            o, _, _ = measure(args, wl, n, mode, 5, 2, brief=True)
             others.append(o)
         out["other_workloads"] = others
     if not args.no_sweep:

@@ -272,6 +272,29 @@ moe_status moe_gran_get(moe_gran* g, const moe_config* cfg, const void* x, const
                         const int32_t* candidates, int32_t n_candidates,
                         int32_t warmup, int32_t iters, int32_t* n, int32_t* searched);
 
+/* ---- performance model of the memory-reuse strategies (Section III-E) ---------------
+ * Strategies: 0 none, 1..4 = S1..S4 of Table II.  Per micro-batch of b tokens a GEMM is
+ * b*H*M multiply-adds, an exchange (here: a local dispatch or combine) and a copy of T_DI
+ * are b*M elements (Eq. 7-9); Table II gives the number of such units per stream and
+ * pass; a pass costs the time of its slowest stream (Eq. 10; the copy term uses eta).
+ *   W_comp multiply-adds/s, W_comm and W_mem elements/s when running alone;
+ *   sigma, mu_*, eta_all: relative speed of computation, exchange and copy when the
+ *   other streams run beside them (mu_comp: beside computation only; *_all: all three).
+ * moe_strategy_cost: seconds per micro-batch, forward and backward.
+ * moe_select_strategy: among the strategies whose bit is set in allowed_mask (bit s =
+ *   strategy s), the one with the least forward + backward cost; ties to the lower
+ *   number.  Non-positive sizes or speeds, unknown strategy, empty mask: MOE_ERR_SHAPE.
+ * Host only.  (S1-S3 need a host-copy stream that this library does not have; their
+ * rows are here for the model's sake.) */
+typedef struct {
+    double W_comp, W_comm, W_mem;
+    double sigma, mu_comp, mu_all, eta_all;
+} moe_speeds;
+moe_status moe_strategy_cost(int32_t strategy, int64_t b, int64_t M, int64_t H, const moe_speeds* speeds,
+                             double* cost_fw, double* cost_bw);
+moe_status moe_select_strategy(uint32_t allowed_mask, int64_t b, int64_t M, int64_t H, const moe_speeds* speeds,
+                               int32_t* best, double* cost);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ EXPORTS = [
     "moe_layer_forward", "moe_layer_backward", "moe_launch_counts", "moe_status_string",
     "moe_last_error", "moe_profile_enable", "moe_profile_read",
     "moe_gran_create", "moe_gran_destroy", "moe_gran_lookup", "moe_gran_record", "moe_gran_ranges",
-    "moe_search_best_gran", "moe_gran_get",
+    "moe_search_best_gran", "moe_gran_get", "moe_strategy_cost", "moe_select_strategy",
 ]
 
 
@@ -304,3 +304,31 @@ def moe_gran_get(g: GranHandle, cfg, x, dy, Wg, gate_bias, W1, W2, y, dx, dWg, d
     _check(lib().moe_gran_get(g._h, *args, cand, ctypes.c_int32(len(candidates)), ctypes.c_int32(warmup),
                               ctypes.c_int32(iters), ctypes.byref(n), ctypes.byref(searched)), "moe_gran_get")
     return n.value, bool(searched.value)
+
+
+# ---- performance model of the reuse strategies -----------------------------------------
+
+class MoESpeeds(ctypes.Structure):
+    _fields_ = [("W_comp", ctypes.c_double), ("W_comm", ctypes.c_double), ("W_mem", ctypes.c_double),
+                ("sigma", ctypes.c_double), ("mu_comp", ctypes.c_double), ("mu_all", ctypes.c_double),
+                ("eta_all", ctypes.c_double)]
+
+
+STRATEGIES = ("none", "S1", "S2", "S3", "S4")
+
+
+def moe_strategy_cost(strategy: int, b: int, M: int, H: int, speeds: MoESpeeds):
+    """(forward, backward) seconds per micro-batch."""
+    fw, bw = ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib().moe_strategy_cost(ctypes.c_int32(strategy), ctypes.c_int64(b), ctypes.c_int64(M), ctypes.c_int64(H),
+                                   ctypes.byref(speeds), ctypes.byref(fw), ctypes.byref(bw)), "moe_strategy_cost")
+    return fw.value, bw.value
+
+
+def moe_select_strategy(allowed_mask: int, b: int, M: int, H: int, speeds: MoESpeeds):
+    """(strategy number, forward + backward seconds)."""
+    best, cost = ctypes.c_int32(0), ctypes.c_double(0)
+    _check(lib().moe_select_strategy(ctypes.c_uint32(allowed_mask), ctypes.c_int64(b), ctypes.c_int64(M),
+                                     ctypes.c_int64(H), ctypes.byref(speeds), ctypes.byref(best), ctypes.byref(cost)),
+           "moe_select_strategy")
+    return best.value, cost.value

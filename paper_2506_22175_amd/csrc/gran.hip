@@ -168,3 +168,65 @@ extern "C" moe_status moe_gran_get(moe_gran* g, const moe_config* cfg, const voi
     if (searched) *searched = 1;
     return moe_gran_record(g, cfg->T, *n);
 }
+
+// ---- performance model of the memory-reuse strategies (Section III-E) ---------------
+// Eq. 7-9: per micro-batch of b tokens one GEMM is b*H*M multiply-adds, one exchange and
+// one copy of T_DI are b*M elements each.  Table II: units per stream in the forward and
+// in the backward pass and the slowdown factors that apply.  Eq. 10: a pass costs what its
+// slowest stream takes (eta in the copy term; the first printed line shows mu there).
+namespace {
+
+struct StrategyRow { int q_fw[3]; int q_bw[3]; bool all_streams; };
+// none, S1, S2, S3, S4
+const StrategyRow kTableII[5] = {
+    {{2, 2, 0}, {4, 2, 0}, false},
+    {{2, 2, 5}, {4, 2, 5}, true},
+    {{2, 2, 4}, {4, 3, 4}, true},
+    {{2, 2, 1}, {5, 2, 1}, true},
+    {{2, 2, 0}, {5, 3, 0}, false},
+};
+
+double pass_cost(const int q[3], double v_comp, double v_io, const moe_speeds& s, double mu, double eta) {
+    const double t_comp = q[0] * v_comp / (s.sigma * s.W_comp);
+    const double t_comm = q[1] * v_io / (mu * s.W_comm);
+    const double t_mem = q[2] ? q[2] * v_io / (eta * s.W_mem) : 0.0;
+    double c = t_comp > t_comm ? t_comp : t_comm;
+    return c > t_mem ? c : t_mem;
+}
+
+bool speeds_ok(const moe_speeds* s) {
+    return s->W_comp > 0 && s->W_comm > 0 && s->W_mem > 0 && s->sigma > 0 && s->mu_comp > 0 && s->mu_all > 0 &&
+           s->eta_all > 0;
+}
+
+}  // namespace
+
+extern "C" moe_status moe_strategy_cost(int32_t strategy, int64_t b, int64_t M, int64_t H, const moe_speeds* speeds,
+                                        double* cost_fw, double* cost_bw) {
+    if (!speeds || !cost_fw || !cost_bw) return MOE_ERR_NULL;
+    if (strategy < 0 || strategy > 4 || b <= 0 || M <= 0 || H <= 0 || !speeds_ok(speeds)) return MOE_ERR_SHAPE;
+    const StrategyRow& r = kTableII[strategy];
+    const double v_comp = (double)b * (double)H * (double)M, v_io = (double)b * (double)M;
+    const double mu = r.all_streams ? speeds->mu_all : speeds->mu_comp;
+    const double eta = r.all_streams ? speeds->eta_all : 1.0;
+    *cost_fw = pass_cost(r.q_fw, v_comp, v_io, *speeds, mu, eta);
+    *cost_bw = pass_cost(r.q_bw, v_comp, v_io, *speeds, mu, eta);
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_select_strategy(uint32_t allowed_mask, int64_t b, int64_t M, int64_t H,
+                                          const moe_speeds* speeds, int32_t* best, double* cost) {
+    if (!speeds || !best) return MOE_ERR_NULL;
+    if ((allowed_mask & 31u) == 0) return MOE_ERR_SHAPE;
+    int pick = -1;
+    double pick_cost = 0.0;
+    for (int s = 0; s < 5; ++s) {
+        if (!((allowed_mask >> s) & 1u)) continue;
+        double fw, bw;
+        MOE_TRY(moe_strategy_cost(s, b, M, H, speeds, &fw, &bw));
+        if (pick < 0 || fw + bw < pick_cost) { pick = s; pick_cost = fw + bw; }
+    }
+    *best = pick;
+    if (cost) *cost = pick_cost;
+    return MOE_OK;
+}
