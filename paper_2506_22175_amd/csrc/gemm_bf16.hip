@@ -38,8 +38,11 @@ constexpr unsigned OOB_OFFSET = 0x80000000u;
 // Buffer descriptor (base, stride 0, size in bytes, raw 32-bit format) kept in SGPRs.
 typedef int v4i __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ v4i make_rsrc(const void* p, unsigned bytes) {
+    // wave-uniform by construction; readfirstlane makes that visible to the compiler, which must
+    // hand the descriptor to the assembly statements below in scalar registers
     const unsigned long long a = (unsigned long long)p;
-    v4i d = {(int)(unsigned)a, (int)((a >> 32) & 0xffffu), (int)bytes, 0x00020000};
+    v4i d = {__builtin_amdgcn_readfirstlane((int)(unsigned)a), __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu)),
+             __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
     return d;
 }
 // 16 bytes per lane from the buffer straight into LDS at lds_off + 16*lane (lds_off is a
@@ -223,6 +226,13 @@ __device__ __forceinline__ void mfma_pinned(floatx16& acc, const bf16x8& a, cons
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b) : "memory");
 }
 
+struct TileCoord { int e, tn, m0, n0, Mdim, Kdim, KT; };
+
+// Persistent workgroups: the grid has one workgroup per CU, and workgroup b works through
+// the tiles b, b + grid, b + 2 grid, ...  While a tile's epilogue runs (it needs only the
+// staging part of LDS and no matrix instructions), the first operand tiles of the next
+// tile are already on their way into the rest of the ring, so neither the launch of a new
+// workgroup nor the first trip to memory stands between two main loops.
 template <int LAY, int EPI, typename C>
 __global__ __launch_bounds__(C::THREADS) __attribute__((amdgpu_waves_per_eu(C::OCC, C::OCC)))
 void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
@@ -230,293 +240,343 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     constexpr int BM = C::BM, BN = C::BN, WM = C::WM, WN = C::WN, TM = C::TM, TNN = C::TN;
     constexpr int STAGE = C::STAGE_BYTES, BK = C::BK, NS = C::NS;
     constexpr int A_BYTES = BM * BK * 2;
+    static_assert(C::PIPE || NS == 2, "ring plans below: five stages of 32 k hand-scheduled, or two stages");
+    // The epilogue stages accumulators in the first SB stages of the ring; a tile's ring
+    // starts at stage SB, so that its first operand tiles can arrive during the epilogue
+    // of the tile before.
+    constexpr int SB = C::PIPE ? 2 : 1;
+    static_assert(C::WAVES * 32 * WN * 4 <= SB * STAGE, "staging does not fit below the ring's first stage");
 
-    // ---- workgroup -> (expert, tile) ------------------------------------------------
-    // Tiles are numbered expert by expert, in groups of 4 tile-rows walked column by
-    // column, so 32 consecutive numbers form a 4 x 8 block that shares 4 A panels and 8
-    // B panels.  Hardware deals consecutive workgroup ids round-robin to the 8 XCDs (each
-    // with its own L2); within every run of 256 workgroups, XCD x is given the x-th block
-    // of 32 consecutive tiles, so each L2 serves a compact block while all eight XCDs
-    // stay on the same expert(s) and share its weights through the memory-side cache.
-    // (Against plain order this halves what the L2s fetch; against giving each XCD its
-    // own experts it is 3-5 % faster.)  A last partial run keeps plain order.
-    int lin;
-    {
-        const int b = blockIdx.x;
-        if (b < (nblocks & ~255)) {
-            const int q = b >> 3;
-            lin = (b & ~255) + (b & 7) * 32 + (q & 31);
-        } else {
-            lin = b;
-        }
-    }
-    const int per_e = tiles_m * tiles_n;
-    const int e = lin / per_e;
-    if (e >= g.E) return;
-    int tm, tn;
-    {
-        const int rem = lin - e * per_e;
-        constexpr int GM = 4;
-        const int grp = rem / (GM * tiles_n);
-        const int first = grp * GM;
-        const int gsz = min(GM, tiles_m - first);
-        const int in = rem - grp * GM * tiles_n;
-        tm = first + in % gsz;
-        tn = in / gsz;
-    }
-    const int rows = g.counts[e];
-    int Mdim, Kdim;
-    if (LAY == GEMM_TN) { Mdim = g.Mo; Kdim = rows; } else { Mdim = rows; Kdim = g.K; }
-    const int m0 = tm * BM, n0 = tn * BN;
-    if (m0 >= Mdim) return;
-    if (Kdim <= 0 && EPI != EPI_STORE_F32) return;    // nothing to add; a plain store still writes zeros
-
-    const bf16_t* A = (const bf16_t*)g.A + (size_t)e * g.a_estride;
-    const bf16_t* B = (const bf16_t*)g.B + (size_t)e * g.b_estride;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wid / C::WAVES_N, wn = wid % C::WAVES_N;
-
     typedef typename ATile<LAY, BM, C::WAVES, BK>::type AT;
     typedef typename BTile<LAY, BN, C::WAVES, BK>::type BT;
-    AT ta;
-    BT tb;
-    ta.init(A, g.lda, m0, Mdim, Kdim, lane, wid);
-    tb.init(B, g.ldb, n0, g.N, Kdim, lane, wid);
+    constexpr int LPW = AT::NI + BT::NI;         // loads per wave per tile
     typename AT::Frag fa[TM];
     typename BT::Frag fb[TNN];
 #pragma unroll
     for (int i = 0; i < TM; ++i) fa[i].init(wm * WM + i * 32, lane);
 #pragma unroll
     for (int j = 0; j < TNN; ++j) fb[j].init(wn * WN + j * 32, lane);
-    const int KT = (Kdim + BK - 1) / BK;
 
-    floatx16 acc[TM][TNN];
+    // ---- tile number -> (expert, tile) -----------------------------------------------
+    // Tiles are numbered expert by expert, in groups of 4 tile-rows walked column by
+    // column, so 32 consecutive numbers form a 4 x 8 block that shares 4 A panels and 8
+    // B panels.  Hardware deals consecutive workgroup ids round-robin to the 8 XCDs (each
+    // with its own L2), and the grid is a multiple of 8, so tile number b always runs on
+    // XCD b mod 8; within every run of 256 numbers, XCD x is given the x-th block of 32
+    // consecutive tiles, so each L2 serves a compact block while all eight XCDs stay on
+    // the same expert(s) and share its weights through the memory-side cache.  (Against
+    // plain order this halves what the L2s fetch; against giving each XCD its own experts
+    // it is 3-5 % faster.)  A last partial run keeps plain order.
+    auto decode = [&](int b, TileCoord& t) -> bool {
+        const int lin = (b < (nblocks & ~255)) ? (b & ~255) + (b & 7) * 32 + ((b >> 3) & 31) : b;
+        const int per_e = tiles_m * tiles_n;
+        const int e = lin / per_e;
+        if (e >= g.E) return false;
+        const int rem = lin - e * per_e;
+        constexpr int GM = 4;
+        const int grp = rem / (GM * tiles_n);
+        const int first = grp * GM;
+        const int gsz = min(GM, tiles_m - first);
+        const int in = rem - grp * GM * tiles_n;
+        const int tm = first + in % gsz;
+        t.tn = in / gsz;
+        const int rows = g.counts[e];
+        if (LAY == GEMM_TN) { t.Mdim = g.Mo; t.Kdim = rows; } else { t.Mdim = rows; t.Kdim = g.K; }
+        t.e = e;
+        t.m0 = tm * BM;
+        t.n0 = t.tn * BN;
+        t.KT = (t.Kdim + BK - 1) / BK;
+        if (t.m0 >= t.Mdim) return false;
+        if (t.Kdim <= 0 && EPI != EPI_STORE_F32) return false;   // nothing to add; a plain store still writes zeros
+        return true;
+    };
+    auto next_tile = [&](int b, TileCoord& t) -> int {          // first tile of this workgroup at or after b, or -1
+        for (; b < nblocks; b += (int)gridDim.x)
+            if (decode(b, t)) return b;
+        return -1;
+    };
+    auto bind = [&](const TileCoord& t, AT& ta_, BT& tb_) {
+        const bf16_t* A = (const bf16_t*)g.A + (size_t)t.e * g.a_estride;
+        const bf16_t* B = (const bf16_t*)g.B + (size_t)t.e * g.b_estride;
+        ta_.init(A, g.lda, t.m0, t.Mdim, t.Kdim, lane, wid);
+        tb_.init(B, g.ldb, t.n0, g.N, t.Kdim, lane, wid);
+    };
+    auto request = [&](const AT& ta_, const BT& tb_, char* st, int k0, int l) {   // load l of the tile starting at k0
+        if (l < AT::NI) ta_.load_one(st, k0, wid, l);
+        else tb_.load_one(st + A_BYTES, k0, wid, l - AT::NI);
+    };
+    // the part of a tile's first loads that does not touch the staging stages, and the rest
+    auto issue_early = [&](const AT& ta_, const BT& tb_) {
+        if constexpr (C::PIPE) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+            for (int s = 0; s < 3; ++s)
 #pragma unroll
-        for (int j = 0; j < TNN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    constexpr int LPW = AT::NI + BT::NI;         // loads per wave per tile
-    if constexpr (C::PIPE) {
-        // One wave per SIMD, so nothing hides a stall: every LDS read and every load into
-        // LDS sits between two matrix instructions, one per instruction, and the data a
-        // block of 16 matrix instructions needs was requested during the block before.
-        // A tile is 32 k = two such blocks; the ring holds five tiles.  In iteration t
-        //   block 0 multiplies k 0..15 of tile t, reads k 16..31 of it into the second
-        //           fragment set and requests the second half of tile t+4;
-        //   then the wave waits for its part of tile t+1 and meets the others (their
-        //           parts have landed too, and nobody reads stage t any more);
-        //   block 1 multiplies k 16..31, reads k 0..15 of tile t+1 into the first
-        //           fragment set and requests the first half of tile t+5 into stage t.
-        // Up to four tiles (128 KB) are in flight towards a CU.
-        static_assert(LPW == 8 && AT::NI == 4 && BT::NI == 4, "load schedule below assumes 4 + 4 loads per wave per tile");
-        auto request = [&](char* st, int k0, int l) {          // load l (0..7) of the tile starting at k0
-            if (l < AT::NI) ta.load_one(st, k0, wid, l);
-            else tb.load_one(st + A_BYTES, k0, wid, l - AT::NI);
-        };
-#pragma unroll
-        for (int s = 0; s < NS - 1; ++s)
-#pragma unroll
-            for (int l = 0; l < LPW; ++l) request(smem + s * STAGE, s * BK, l);
-#pragma unroll
-        for (int l = 0; l < LPW / 2; ++l) request(smem + (NS - 1) * STAGE, (NS - 1) * BK, l);
-        wait_vmcnt<3 * LPW + LPW / 2>();                        // tile 0 is in
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        bf16x8 F0[8], F1[8];
-#pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            F0[f] = fa[f].read(smem, 0);
-            F0[4 + f] = fb[f].read(smem + A_BYTES, 0);
+                for (int l = 0; l < LPW; ++l) request(ta_, tb_, smem + (SB + s) * STAGE, s * BK, l);
+        } else {
+            ta_.load(smem + SB * STAGE, 0, wid);
+            tb_.load(smem + SB * STAGE + A_BYTES, 0, wid);
         }
-        int st = 0;
+    };
+    auto issue_late = [&](const AT& ta_, const BT& tb_) {
+        if constexpr (C::PIPE) {
+#pragma unroll
+            for (int l = 0; l < LPW; ++l) request(ta_, tb_, smem, 3 * BK, l);
+#pragma unroll
+            for (int l = 0; l < LPW / 2; ++l) request(ta_, tb_, smem + STAGE, 4 * BK, l);
+        }
+    };
+
+    TileCoord cur;
+    int vb = next_tile(blockIdx.x, cur);
+    if (vb < 0) return;
+    AT ta;
+    BT tb;
+    bind(cur, ta, tb);
+    issue_early(ta, tb);
+    issue_late(ta, tb);
+    bool first = true;
+
+    for (;;) {
+        const int m0 = cur.m0, n0 = cur.n0, e = cur.e, tn = cur.tn, Mdim = cur.Mdim, KT = cur.KT;
+        floatx16 acc[TM][TNN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TNN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+        if constexpr (C::PIPE) {
+            // One wave per SIMD, so nothing hides a stall: every LDS read and every load into
+            // LDS sits between two matrix instructions, one per instruction, and the data a
+            // block of 16 matrix instructions needs was requested during the block before.
+            // A tile is 32 k = two such blocks; the ring holds five tiles.  In iteration t
+            //   block 0 multiplies k 0..15 of tile t, reads k 16..31 of it into the second
+            //           fragment set and requests the second half of tile t+4;
+            //   then the wave waits for its part of tile t+1 and meets the others (their
+            //           parts have landed too, and nobody reads stage t any more);
+            //   block 1 multiplies k 16..31, reads k 0..15 of tile t+1 into the first
+            //           fragment set and requests the first half of tile t+5 into stage t.
+            // Up to four tiles (128 KB) are in flight towards a CU.  (Stores of the
+            // previous epilogue may still be counted by vmcnt; they are older than the
+            // loads waited for, so the counts below only become stricter.)
+            static_assert(LPW == 8 && AT::NI == 4 && BT::NI == 4, "load schedule below assumes 4 + 4 loads per wave per tile");
+            if (first) wait_vmcnt<3 * LPW + LPW / 2>();            // tile 0 is in (later tiles: waited for in the epilogue)
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            bf16x8 F0[8], F1[8];
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                F0[f] = fa[f].read(smem + SB * STAGE, 0);
+                F0[4 + f] = fb[f].read(smem + SB * STAGE + A_BYTES, 0);
+            }
+            int st = SB;
 #pragma unroll 1
-        for (int kt = 0; kt < KT; ++kt) {
-            char* cur = smem + st * STAGE;
-            const int stn = (st + 1 == NS) ? 0 : st + 1;
-            const int stp = (st == 0) ? NS - 1 : st - 1;
-            char* nxt = smem + stn * STAGE;
-            char* prv = smem + stp * STAGE;
+            for (int kt = 0; kt < KT; ++kt) {
+                char* cs = smem + st * STAGE;
+                const int stn = (st + 1 == NS) ? 0 : st + 1;
+                const int stp = (st == 0) ? NS - 1 : st - 1;
+                char* nxt = smem + stn * STAGE;
+                char* prv = smem + stp * STAGE;
 #pragma unroll
-            for (int m = 0; m < 16; ++m) {
-                mfma_pinned(acc[m >> 2][m & 3], F0[4 + (m & 3)], F0[m >> 2]);
-                if (m < 4) F1[m] = fa[m].read(cur, 1);
-                else if (m < 8) F1[m] = fb[m - 4].read(cur + A_BYTES, 1);
-                else if (m < 12) request(prv, (kt + 4) * BK, LPW / 2 + m - 8);
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave no longer reads stage t
-            wait_vmcnt<3 * LPW>();                               // its part of tile t+1 is in
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
+                for (int m = 0; m < 16; ++m) {
+                    mfma_pinned(acc[m >> 2][m & 3], F0[4 + (m & 3)], F0[m >> 2]);
+                    if (m < 4) F1[m] = fa[m].read(cs, 1);
+                    else if (m < 8) F1[m] = fb[m - 4].read(cs + A_BYTES, 1);
+                    else if (m < 12) request(ta, tb, prv, (kt + 4) * BK, LPW / 2 + m - 8);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave no longer reads stage t
+                wait_vmcnt<3 * LPW>();                               // its part of tile t+1 is in
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
 #pragma unroll
-            for (int m = 0; m < 16; ++m) {
-                mfma_pinned(acc[m >> 2][m & 3], F1[4 + (m & 3)], F1[m >> 2]);
-                if (m < 4) F0[m] = fa[m].read(nxt, 0);
-                else if (m < 8) F0[m] = fb[m - 4].read(nxt + A_BYTES, 0);
-                else if (m < 12) request(cur, (kt + 5) * BK, m - 8);
+                for (int m = 0; m < 16; ++m) {
+                    mfma_pinned(acc[m >> 2][m & 3], F1[4 + (m & 3)], F1[m >> 2]);
+                    if (m < 4) F0[m] = fa[m].read(nxt, 0);
+                    else if (m < 8) F0[m] = fb[m - 4].read(nxt + A_BYTES, 0);
+                    else if (m < 12) request(ta, tb, cs, (kt + 5) * BK, m - 8);
+                }
+                st = stn;
             }
-            st = stn;
-        }
-        // the assembler-level matrix instructions are invisible to the compiler's hazard
-        // checks: let the last of them retire before anything reads the accumulators
-        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-    } else {
-        // Ring of NS stages.  Tiles 0 .. NS-2 are requested up front; in iteration kt
-        // the wave waits until its own part of tile kt has landed (the NS-2 younger
-        // tiles may still be in flight), the barrier makes every wave's part visible
-        // and tells that tile kt-1 has been consumed, whose stage then receives tile
-        // kt+NS-1.  A tile past the end reads as zeros.
-    #pragma unroll
-        for (int s = 0; s < NS - 1; ++s) {
-            ta.load(smem + s * STAGE, s * BK, wid);
-            tb.load(smem + s * STAGE + A_BYTES, s * BK, wid);
-        }
-        int st_cur = 0, st_free = NS - 1;
-        for (int kt = 0; kt < KT; ++kt) {
-            wait_vmcnt<(NS - 2) * LPW>();
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            char* cur = smem + st_cur * STAGE;
-            char* nxt = smem + st_free * STAGE;
-            ta.load(nxt, (kt + NS - 1) * BK, wid);
-            tb.load(nxt + A_BYTES, (kt + NS - 1) * BK, wid);
-    #pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk) {
-                bf16x8 af[TM], bfr[TNN];
-    #pragma unroll
-                for (int i = 0; i < TM; ++i) af[i] = fa[i].read(cur, kk);
-    #pragma unroll
-                for (int j = 0; j < TNN; ++j) bfr[j] = fb[j].read(cur + A_BYTES, kk);
-    #pragma unroll
-                for (int i = 0; i < TM; ++i)
-    #pragma unroll
-                    for (int j = 0; j < TNN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+            // the assembler-level matrix instructions are invisible to the compiler's hazard
+            // checks: let the last of them retire before anything reads the accumulators
+            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        } else {
+            // Ring of two stages.  In iteration kt the wave waits until its own part of tile
+            // kt has landed, the barrier makes every wave's part visible and tells that tile
+            // kt-1 has been consumed, whose stage then receives tile kt+1.  A tile past the
+            // end reads as zeros.
+            int st_cur = SB, st_free = SB ^ 1;
+            for (int kt = 0; kt < KT; ++kt) {
+                if (kt > 0 || first) wait_vmcnt<0>();                // (a later tile's tile 0: waited for in the epilogue)
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                char* cs = smem + st_cur * STAGE;
+                char* nxt = smem + st_free * STAGE;
+                ta.load(nxt, (kt + 1) * BK, wid);
+                tb.load(nxt + A_BYTES, (kt + 1) * BK, wid);
+#pragma unroll
+                for (int kk = 0; kk < BK / 16; ++kk) {
+                    bf16x8 af[TM], bfr[TNN];
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) af[i] = fa[i].read(cs, kk);
+#pragma unroll
+                    for (int j = 0; j < TNN; ++j) bfr[j] = fb[j].read(cs + A_BYTES, kk);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TNN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+                }
+                st_free = st_cur;
+                st_cur ^= 1;
             }
-            st_free = st_cur;
-            st_cur = (st_cur + 1 == NS) ? 0 : st_cur + 1;
         }
-    }
-    wait_vmcnt<0>();                             // nothing of this workgroup is in flight into LDS any more
-    __builtin_amdgcn_s_barrier();                // and every wave is done reading the ring
-    asm volatile("" ::: "memory");
+        wait_vmcnt<0>();                             // nothing of this workgroup is in flight into LDS any more
+        __builtin_amdgcn_s_barrier();                // and every wave is done reading the ring
+        asm volatile("" ::: "memory");
 
-    // ---- epilogue -----------------------------------------------------------------------
-    // An MFMA accumulator holds one row per lane (row = lane & 31, four consecutive
-    // columns per register group), which would make every global access a 8- or 16-byte
-    // piece of 32 different rows.  Each wave therefore passes its 32 x WN blocks through a
-    // private LDS region (float, 16-byte chunks XOR-swizzled by row) and picks them up
-    // with eight consecutive columns per lane, so that eight lanes cover a whole line of
-    // a row: all global reads and writes of the epilogue are 16 or 32 bytes per lane,
-    // row-contiguous.  They go through buffer descriptors that end after the last valid
-    // row, so there is no branch: out-of-range reads give zero, out-of-range writes are
-    // dropped, and all reads of a 32-row pass are issued before the arithmetic starts.
-    constexpr int CPRW = WN / 8;                 // 8-column pieces per row of the wave's block
-    constexpr int NPIECE = 32 * CPRW / 64;       // pieces per lane
-    float* stage = reinterpret_cast<float*>(smem + wid * (32 * WN * 4));
-    static_assert(C::WAVES * 32 * WN * 4 <= C::LDS_BYTES, "staging does not fit");
-    constexpr int CES = (EPI == EPI_ACCUM_F32 || EPI == EPI_STORE_F32) ? 4 : 2;   // bytes per output element
-    const char* Cbase = (const char*)g.C + (size_t)e * g.c_estride * CES;
-    const __amdgpu_buffer_rsrc_t rC = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<char*>(Cbase), 0, (unsigned)(((size_t)(Mdim - 1) * g.ldc + g.N) * CES), 0x00020000);
-    const bf16_t* Zbase = g.Z ? (const bf16_t*)g.Z + (size_t)e * g.Cp * g.ldz : nullptr;
-    const __amdgpu_buffer_rsrc_t rZ = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t*>(Zbase), 0, Zbase ? (unsigned)(((size_t)(Mdim - 1) * g.ldz + g.N) * 2) : 0u, 0x00020000);
-    const float* wbase = g.slot_w ? g.slot_w + (size_t)e * g.Cp : nullptr;
-    const int erow = lane & 31, ehalf = lane >> 5;
+        // ---- the tile after this one ------------------------------------------------------
+        TileCoord nx;
+        AT ta2;
+        BT tb2;
+        const int vn = next_tile(vb + (int)gridDim.x, nx);
+        if (vn >= 0) bind(nx, ta2, tb2);
+
+        // ---- epilogue -----------------------------------------------------------------------
+        // An MFMA accumulator holds one row per lane (row = lane & 31, four consecutive
+        // columns per register group), which would make every global access a 8- or 16-byte
+        // piece of 32 different rows.  Each wave therefore passes its 32 x WN blocks through a
+        // private LDS region (float, 16-byte chunks XOR-swizzled by row) and picks them up
+        // with eight consecutive columns per lane, so that eight lanes cover a whole line of
+        // a row: all global reads and writes of the epilogue are 16 or 32 bytes per lane,
+        // row-contiguous.  They go through buffer descriptors that end after the last valid
+        // row, so there is no branch: out-of-range reads give zero, out-of-range writes are
+        // dropped, and all reads of a 32-row pass are issued before the arithmetic starts.
+        constexpr int CPRW = WN / 8;                 // 8-column pieces per row of the wave's block
+        constexpr int NPIECE = 32 * CPRW / 64;       // pieces per lane
+        float* stage = reinterpret_cast<float*>(smem + wid * (32 * WN * 4));
+        constexpr int CES = (EPI == EPI_ACCUM_F32 || EPI == EPI_STORE_F32) ? 4 : 2;   // bytes per output element
+        const char* Cbase = (const char*)g.C + (size_t)e * g.c_estride * CES;
+        const __amdgpu_buffer_rsrc_t rC = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(Cbase), 0, (unsigned)(((size_t)(Mdim - 1) * g.ldc + g.N) * CES), 0x00020000);
+        const bf16_t* Zbase = g.Z ? (const bf16_t*)g.Z + (size_t)e * g.Cp * g.ldz : nullptr;
+        const __amdgpu_buffer_rsrc_t rZ = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<bf16_t*>(Zbase), 0, Zbase ? (unsigned)(((size_t)(Mdim - 1) * g.ldz + g.N) * 2) : 0u, 0x00020000);
+        const float* wbase = g.slot_w ? g.slot_w + (size_t)e * g.Cp : nullptr;
+        const int erow = lane & 31, ehalf = lane >> 5;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+        for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int j = 0; j < TNN; ++j) {
+            for (int j = 0; j < TNN; ++j) {
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int cch = (j * 32 + g4 * 8 + ehalf * 4) >> 2;
-                float4 v = make_float4(acc[i][j][g4 * 4 + 0], acc[i][j][g4 * 4 + 1], acc[i][j][g4 * 4 + 2], acc[i][j][g4 * 4 + 3]);
-                *reinterpret_cast<float4*>(stage + erow * WN + ((cch ^ (erow & 15)) << 2)) = v;
-            }
-        }
-        // operands of this pass from memory, all requested before any is used
-        int pm[NPIECE];
-        unsigned offC[NPIECE], offZ[NPIECE];
-        uint4 zin[NPIECE];
-        float4 cin0[NPIECE], cin1[NPIECE];
-        float wrow[NPIECE];
-#pragma unroll
-        for (int t = 0; t < NPIECE; ++t) {
-            const int idx = lane + 64 * t;
-            const int row = idx / CPRW, c8 = idx % CPRW;
-            const int m = m0 + wm * WM + i * 32 + row;
-            const int n = n0 + wn * WN + c8 * 8;
-            pm[t] = m;
-            const bool in = n < g.N;             // rows beyond Mdim fall outside the descriptors by themselves
-            offC[t] = in ? (unsigned)(m * g.ldc + n) * CES : OOB_OFFSET;
-            offZ[t] = in ? (unsigned)(m * g.ldz + n) * 2u : OOB_OFFSET;
-            if constexpr (EPI == EPI_DGELU) {
-                zin[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rZ, offZ[t], 0, 0));
-                wrow[t] = m < Mdim ? wbase[m] : 0.0f;
-            }
-            if constexpr (EPI == EPI_ACCUM_F32) {
-                cin0[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, offC[t], 0, 0));
-                cin1[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, offC[t] + 16u, 0, 0));
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < NPIECE; ++t) {
-            const int idx = lane + 64 * t;
-            const int row = idx / CPRW, c8 = idx % CPRW;
-            const float4 lo = *reinterpret_cast<const float4*>(stage + row * WN + (((2 * c8) ^ (row & 15)) << 2));
-            const float4 hi = *reinterpret_cast<const float4*>(stage + row * WN + (((2 * c8 + 1) ^ (row & 15)) << 2));
-            float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            if constexpr (EPI == EPI_STORE) {
-                uint4 o = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o), rC, offC[t], 0, 0);
-            } else if constexpr (EPI == EPI_GELU) {
-                float z[8], a[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q) { z[q] = bf16_to_f32(f32_to_bf16(v[q])); a[q] = gelu_f(z[q]); }
-                uint4 oz = make_uint4(pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3]), pack_bf16x2(z[4], z[5]), pack_bf16x2(z[6], z[7]));
-                uint4 oa = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
-                if (Zbase) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oz), rZ, offZ[t], 0, 0);
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oa), rC, offC[t], 0, 0);
-            } else if constexpr (EPI == EPI_DGELU) {
-                float z[8], dz[8], a[8];
-                Unit8::to_float(zin[t], z);
-                const float w = wrow[t];
-                float dot = 0.0f;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    float gq, dg;
-                    gelu_both_f(z[q], &gq, &dg);
-                    dot = fmaf(gq, v[q], dot);
-                    a[q] = w * gq;
-                    dz[q] = w * v[q] * dg;
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int cch = (j * 32 + g4 * 8 + ehalf * 4) >> 2;
+                    float4 v = make_float4(acc[i][j][g4 * 4 + 0], acc[i][j][g4 * 4 + 1], acc[i][j][g4 * 4 + 2], acc[i][j][g4 * 4 + 3]);
+                    *reinterpret_cast<float4*>(stage + erow * WN + ((cch ^ (erow & 15)) << 2)) = v;
                 }
-                uint4 od = make_uint4(pack_bf16x2(dz[0], dz[1]), pack_bf16x2(dz[2], dz[3]), pack_bf16x2(dz[4], dz[5]), pack_bf16x2(dz[6], dz[7]));
-                uint4 oa = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, od), rC, offC[t], 0, 0);
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oa), rZ, offZ[t], 0, 0);
-                if (g.dw_part) {
-                    // the CPRW lanes of a row are neighbours; rows and columns out of range gave zeros
-                    if (!(pm[t] < Mdim && offC[t] != OOB_OFFSET)) dot = 0.0f;
-#pragma unroll
-                    for (int off = CPRW / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
-                    if (c8 == 0 && pm[t] < Mdim)
-                        g.dw_part[((size_t)e * g.Cp + pm[t]) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
-                }
-            } else if constexpr (EPI == EPI_STORE_F32) {
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, lo), rC, offC[t], 0, 0);
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, hi), rC, offC[t] + 16u, 0, 0);
-            } else {
-                float4 o0 = cin0[t], o1 = cin1[t];
-                o0.x += v[0]; o0.y += v[1]; o0.z += v[2]; o0.w += v[3];
-                o1.x += v[4]; o1.y += v[5]; o1.z += v[6]; o1.w += v[7];
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o0), rC, offC[t], 0, 0);
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o1), rC, offC[t] + 16u, 0, 0);
             }
+            // operands of this pass from memory, all requested before any is used
+            int pm[NPIECE];
+            unsigned offC[NPIECE], offZ[NPIECE];
+            uint4 zin[NPIECE];
+            float4 cin0[NPIECE], cin1[NPIECE];
+            float wrow[NPIECE];
+#pragma unroll
+            for (int t = 0; t < NPIECE; ++t) {
+                const int idx = lane + 64 * t;
+                const int row = idx / CPRW, c8 = idx % CPRW;
+                const int m = m0 + wm * WM + i * 32 + row;
+                const int n = n0 + wn * WN + c8 * 8;
+                pm[t] = m;
+                const bool in = n < g.N;             // rows beyond Mdim fall outside the descriptors by themselves
+                offC[t] = in ? (unsigned)(m * g.ldc + n) * CES : OOB_OFFSET;
+                offZ[t] = in ? (unsigned)(m * g.ldz + n) * 2u : OOB_OFFSET;
+                if constexpr (EPI == EPI_DGELU) {
+                    zin[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rZ, offZ[t], 0, 0));
+                    wrow[t] = m < Mdim ? wbase[m] : 0.0f;
+                }
+                if constexpr (EPI == EPI_ACCUM_F32) {
+                    cin0[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, offC[t], 0, 0));
+                    cin1[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, offC[t] + 16u, 0, 0));
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < NPIECE; ++t) {
+                const int idx = lane + 64 * t;
+                const int row = idx / CPRW, c8 = idx % CPRW;
+                const float4 lo = *reinterpret_cast<const float4*>(stage + row * WN + (((2 * c8) ^ (row & 15)) << 2));
+                const float4 hi = *reinterpret_cast<const float4*>(stage + row * WN + (((2 * c8 + 1) ^ (row & 15)) << 2));
+                float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                if constexpr (EPI == EPI_STORE) {
+                    uint4 o = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o), rC, offC[t], 0, 0);
+                } else if constexpr (EPI == EPI_GELU) {
+                    float z[8], a[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) { z[q] = bf16_to_f32(f32_to_bf16(v[q])); a[q] = gelu_f(z[q]); }
+                    uint4 oz = make_uint4(pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3]), pack_bf16x2(z[4], z[5]), pack_bf16x2(z[6], z[7]));
+                    uint4 oa = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
+                    if (Zbase) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oz), rZ, offZ[t], 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oa), rC, offC[t], 0, 0);
+                } else if constexpr (EPI == EPI_DGELU) {
+                    float z[8], dz[8], a[8];
+                    Unit8::to_float(zin[t], z);
+                    const float w = wrow[t];
+                    float dot = 0.0f;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        float gq, dg;
+                        gelu_both_f(z[q], &gq, &dg);
+                        dot = fmaf(gq, v[q], dot);
+                        a[q] = w * gq;
+                        dz[q] = w * v[q] * dg;
+                    }
+                    uint4 od = make_uint4(pack_bf16x2(dz[0], dz[1]), pack_bf16x2(dz[2], dz[3]), pack_bf16x2(dz[4], dz[5]), pack_bf16x2(dz[6], dz[7]));
+                    uint4 oa = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, od), rC, offC[t], 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oa), rZ, offZ[t], 0, 0);
+                    if (g.dw_part) {
+                        // the CPRW lanes of a row are neighbours; rows and columns out of range gave zeros
+                        if (!(pm[t] < Mdim && offC[t] != OOB_OFFSET)) dot = 0.0f;
+#pragma unroll
+                        for (int off = CPRW / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
+                        if (c8 == 0 && pm[t] < Mdim)
+                            g.dw_part[((size_t)e * g.Cp + pm[t]) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
+                    }
+                } else if constexpr (EPI == EPI_STORE_F32) {
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, lo), rC, offC[t], 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, hi), rC, offC[t] + 16u, 0, 0);
+                } else {
+                    float4 o0 = cin0[t], o1 = cin1[t];
+                    o0.x += v[0]; o0.y += v[1]; o0.z += v[2]; o0.w += v[3];
+                    o1.x += v[4]; o1.y += v[5]; o1.z += v[6]; o1.w += v[7];
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o0), rC, offC[t], 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o1), rC, offC[t] + 16u, 0, 0);
+                }
+            }
+            // the next tile's first operand tiles start their trip once the first pass is through
+            // (earlier, and this pass's own reads would have to wait behind them)
+            if (i == 0 && vn >= 0) issue_early(ta2, tb2);
         }
+        if (vn < 0) break;
+        // Tile 0 of the next tile has landed: its loads were issued after the first pass, every
+        // later pass issued at least NPIECE stores per wave, and memory operations retire in
+        // order, so whatever may still be counted is younger.
+        constexpr int ALLOW = C::PIPE ? 2 * LPW : LPW;
+        static_assert((TM - 1) * NPIECE >= ALLOW, "not enough younger stores to hide behind");
+        wait_vmcnt<ALLOW>();
+        __builtin_amdgcn_s_barrier();                // every wave is done with the staging stages
+        asm volatile("" ::: "memory");
+        issue_late(ta2, tb2);
+        ta = ta2;
+        tb = tb2;
+        cur = nx;
+        vb = vn;
+        first = false;
     }
 }
 
@@ -549,12 +609,27 @@ typedef CfgFor<EPI_DGELU>::type CfgDgelu;
 
 int gemm_bf16_dw_parts(int H) { return ((H + CfgDgelu::BN - 1) / CfgDgelu::BN) * CfgDgelu::WAVES_N; }
 
+// One workgroup per CU (a workgroup fills a CU's LDS), rounded down to a multiple of 8 so that
+// tile numbers keep their XCD.
+static int persistent_grid() {
+    static int grid = 0;
+    if (grid == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+            cus = 256;
+        grid = cus / 8 * 8;
+    }
+    return grid;
+}
+
 template <int LAY, int EPI, typename C>
 static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
     const int Mmax = (LAY == GEMM_TN) ? a.Mo : a.Cp;
     const int tiles_m = (Mmax + C::BM - 1) / C::BM, tiles_n = (a.N + C::BN - 1) / C::BN;
     int nblocks = a.E * tiles_m * tiles_n;
     nblocks = (nblocks + 7) / 8 * 8;
+    const int grid = nblocks < persistent_grid() ? nblocks : persistent_grid();
     constexpr int lds = C::LDS_BYTES;
     auto kern = gemm_bf16_kernel<LAY, EPI, C>;
     static bool attr_done = false;
@@ -564,7 +639,7 @@ static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
     }
     {
         ProfScope ps(gemm_prof_kind(LAY, EPI), s);
-        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(C::THREADS), lds, s, a, tiles_m, tiles_n, nblocks);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(C::THREADS), lds, s, a, tiles_m, tiles_n, nblocks);
     }
     count_launch(LC_GEMM);
     MOE_CHECK_LAUNCH();
