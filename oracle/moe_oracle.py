@@ -147,12 +147,18 @@ def top_k(logits: np.ndarray, k: int) -> np.ndarray:
     return order[:, :k].astype(np.int32)
 
 
-def route(x, Wg, k: int, bias=None):
-    """logits (float32), probabilities (float64), chosen experts and their weights."""
+def route(x, Wg, k: int, bias=None, renormalize: bool = False):
+    """logits (float32), probabilities (float64), chosen experts and their weights.
+
+    renormalize (a gate variant the paper does not use: it runs k = 1, where this would
+    make every weight 1): the chosen probabilities are divided by their sum over the k
+    choices of the token, before any drop."""
     logits = gate_logits(x, Wg, bias)
     p = softmax_rows(logits)
     idx = top_k(logits, k)
     w = np.take_along_axis(p, idx.astype(np.int64), axis=1)
+    if renormalize:
+        w = w / w.sum(axis=1, keepdims=True)
     return logits, p, idx, w
 
 
@@ -197,7 +203,7 @@ def gelu_grad(z):
 # --------------------------------------------------------------------------
 
 def layer_step(x, Wg, W1, W2, dy, k: int, capacity_factor: float, n: int = 1,
-               gate_bias=None, keep_intermediates: bool = False) -> Dict[str, np.ndarray]:
+               gate_bias=None, keep_intermediates: bool = False, renormalize: bool = False) -> Dict[str, np.ndarray]:
     """Forward and backward of the MoE layer over T tokens split into n partitions.
 
     x [T,M], Wg [M,E], W1 [E,M,H], W2 [E,H,M], dy [T,M] (upstream gradient).
@@ -208,7 +214,7 @@ def layer_step(x, Wg, W1, W2, dy, k: int, capacity_factor: float, n: int = 1,
     E, _, H = W1.shape
     C_p = capacity(T, E, k, capacity_factor, n)
     T_p = T // n
-    logits, p, idx, w = route(x, Wg, k, gate_bias)
+    logits, p, idx, w = route(x, Wg, k, gate_bias, renormalize)
     slot, counts = assign_slots(idx, E, C_p, n)
 
     X = x.astype(np.float64)
@@ -256,8 +262,14 @@ def layer_step(x, Wg, W1, W2, dy, k: int, capacity_factor: float, n: int = 1,
                 inter[(part, e)] = dict(tokens=tt, choice=jj, DI=DI, Z=Z, O=O, dO=dO, dZ=dZ, dDI=dDI)
 
     # gate backward: softmax Jacobian on the chosen probabilities
+    dp_sel = dw
+    if renormalize:
+        # w_j = p_j / S with S the sum of the chosen probabilities: d/dp_j = dw_j / S - sum_j' dw_j' p_j' / S^2
+        p_sel = np.take_along_axis(p, idx.astype(np.int64), axis=1)
+        S = p_sel.sum(axis=1, keepdims=True)
+        dp_sel = dw / S - (dw * p_sel).sum(axis=1, keepdims=True) / (S * S)
     dp = np.zeros((T, E))
-    np.put_along_axis(dp, idx.astype(np.int64), dw, axis=1)
+    np.put_along_axis(dp, idx.astype(np.int64), dp_sel, axis=1)
     dL = p * (dp - (dp * p).sum(axis=1, keepdims=True))
     dWg = X.T @ dL
     dx += dL @ Wgd.T

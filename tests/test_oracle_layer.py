@@ -83,7 +83,7 @@ def test_forward_matches_scalar_loops_with_drops(oracle):
 
 # ---------- backward against automatic differentiation --------------------------
 
-def _torch_layer(d, idx, slot, k):
+def _torch_layer(d, idx, slot, k, renormalize=False):
     """Forward definition in torch (float64) with routing held constant."""
     x = torch.tensor(d["x"], dtype=torch.float64, requires_grad=True)
     Wg = torch.tensor(d["Wg"], dtype=torch.float64, requires_grad=True)
@@ -97,11 +97,13 @@ def _torch_layer(d, idx, slot, k):
     rows = []
     for t in range(x.shape[0]):
         acc = torch.zeros(x.shape[1], dtype=torch.float64)
+        chosen = sum(p[t, int(idx[t, j])] for j in range(k))         # over all k choices, dropped ones included
         for j in range(k):
             if slot[t, j] < 0:
                 continue
             e = int(idx[t, j])
-            acc = acc + p[t, e] * (torch.nn.functional.gelu(x[t] @ W1[e]) @ W2[e])
+            wgt = p[t, e] / chosen if renormalize else p[t, e]
+            acc = acc + wgt * (torch.nn.functional.gelu(x[t] @ W1[e]) @ W2[e])
         rows.append(acc)
     y = torch.stack(rows)
     return x, Wg, W1, W2, y
@@ -122,6 +124,32 @@ def test_backward_matches_autograd_of_the_forward_definition(oracle, T, M, H, E,
     for name, g in (("dx", x.grad), ("dWg", Wg.grad), ("dW1", W1.grad), ("dW2", W2.grad)):
         ref = g.numpy()
         assert np.abs(r[name] - ref).max() <= 1e-6 * np.abs(ref).max() + 1e-12, name
+
+
+@pytest.mark.parametrize("T,M,H,E,k,cf,n", [(16, 64, 16, 4, 2, 1.0, 1), (24, 8, 12, 5, 3, 0.75, 2), (12, 8, 8, 3, 3, 1.0, 1)])
+def test_renormalised_gate_variant_matches_autograd_of_its_definition(oracle, T, M, H, E, k, cf, n):
+    """Chosen probabilities divided by their sum over the token's k choices (drops do not change the sum)."""
+    s, d = _inputs(T, M, H, E, k, cf, seed=100 + T)
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], k, cf, n, renormalize=True)
+    assert np.allclose(r["w"].sum(axis=1), 1.0, rtol=0, atol=1e-12)
+    plain = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], k, cf, n)
+    assert np.array_equal(r["idx"], plain["idx"]) and np.array_equal(r["slot"], plain["slot"])
+    if k == E:                                    # every expert chosen: the sum is 1 already
+        assert np.allclose(r["w"], plain["w"], rtol=1e-12) and np.allclose(r["dWg"], plain["dWg"], rtol=1e-9, atol=1e-15)
+    x, Wg, W1, W2, y = _torch_layer(d, r["idx"], r["slot"], k, renormalize=True)
+    y.backward(torch.tensor(d["dy"], dtype=torch.float64))
+    yr = y.detach().numpy()
+    assert np.abs(r["y"] - yr).max() <= 1e-6 * np.abs(yr).max()
+    for name, g in (("dx", x.grad), ("dWg", Wg.grad), ("dW1", W1.grad), ("dW2", W2.grad)):
+        ref = g.numpy()
+        assert np.abs(r[name] - ref).max() <= 1e-6 * np.abs(ref).max() + 1e-12, name
+
+
+def test_renormalised_gate_with_one_choice_has_weight_one_and_no_gate_gradient(oracle):
+    s, d = _inputs(32, 16, 8, 4, 1, 1.0, seed=5)
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], 1, 1.0, 1, renormalize=True)
+    assert np.all(r["w"] == 1.0)
+    assert np.abs(r["dWg"]).max() <= 1e-12 * max(1.0, np.abs(r["dW1"]).max())
 
 
 def test_backward_matches_central_finite_differences(oracle):
