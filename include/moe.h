@@ -66,6 +66,10 @@ typedef struct {
                                1: calls for partition 0 store, calls for later partitions
                                accumulate, so one pass over partitions 0..n-1 leaves the
                                gradients of this step whatever the buffers held before */
+    int32_t gate_renormalize; /* 0: combine weights are the chosen softmax probabilities
+                               (what the paper's k = 1 gate implies); 1: they are divided
+                               by their sum over the token's k choices, drops included
+                               (a softmax over the chosen logits only) */
 } moe_config;
 
 /* Host only.  C_p = ceil(capacity_factor * k * (T / n) / E), evaluated in double

@@ -123,6 +123,7 @@ struct Dims {
     int T, M, H, E, k, n, Tp, Cp, Rp;
     int dtype, reuse;
     int overwrite;   // weight gradients are overwritten (first partition stores) instead of accumulated
+    int renorm;      // combine weights are renormalised over the token's k choices
     size_t es;   // element size in bytes
 };
 

@@ -26,6 +26,7 @@ moe_status make_dims(const moe_config* cfg, Dims* d) {
     d->Rp = d->Cp * d->E;
     d->dtype = cfg->dtype; d->reuse = cfg->reuse;
     d->overwrite = cfg->grad_overwrite != 0;
+    d->renorm = cfg->gate_renormalize != 0;
     d->es = cfg->dtype == MOE_F32 ? 4 : 2;
     return MOE_OK;
 }

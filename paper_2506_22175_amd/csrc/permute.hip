@@ -303,21 +303,38 @@ __global__ __launch_bounds__(PERM_THREADS) void dispatch_bwd_kernel(
 // chosen experts; one thread per token.
 __device__ __forceinline__ void gate_dl_token(
     const float* __restrict__ logits, const int* __restrict__ topk_idx, const float* dw_t,
-    float* __restrict__ dL, float* sdl, int t, int E, int k) {
+    float* __restrict__ dL, float* sdl, int t, int E, int k, int renorm) {
     const float* lg = logits + (size_t)t * E;
     float mx = -INFINITY;
     for (int e = 0; e < E; ++e) mx = fmaxf(mx, lg[e]);
-    float sum = 0.0f;
-    for (int e = 0; e < E; ++e) sum += expf(lg[e] - mx);
-    const float inv = 1.0f / sum;
     float g[8];
     int ids[8];
-    float inner = 0.0f;
     for (int j = 0; j < k; ++j) {
         ids[j] = topk_idx[(size_t)t * k + j];
         g[j] = dw_t[j];
-        inner = fmaf(g[j], expf(lg[ids[j]] - mx) * inv, inner);
     }
+    if (renorm) {
+        // weights are a softmax over the chosen logits only: dL_e = w_j (dw_j - sum_j' dw_j' w_j')
+        // for a chosen e, zero otherwise
+        float den = 0.0f;
+        for (int j = 0; j < k; ++j) den += expf(lg[ids[j]] - mx);
+        const float inv = 1.0f / den;
+        float inner = 0.0f;
+        for (int j = 0; j < k; ++j) inner = fmaf(g[j], expf(lg[ids[j]] - mx) * inv, inner);
+        for (int e = 0; e < E; ++e) {
+            float v = 0.0f;
+            for (int j = 0; j < k; ++j)
+                if (ids[j] == e) v = expf(lg[e] - mx) * inv * (g[j] - inner);
+            dL[(size_t)t * E + e] = v;
+            sdl[e] = v;
+        }
+        return;
+    }
+    float sum = 0.0f;
+    for (int e = 0; e < E; ++e) sum += expf(lg[e] - mx);
+    const float inv = 1.0f / sum;
+    float inner = 0.0f;
+    for (int j = 0; j < k; ++j) inner = fmaf(g[j], expf(lg[ids[j]] - mx) * inv, inner);
     for (int e = 0; e < E; ++e) {
         float p = expf(lg[e] - mx) * inv;
         float dp = 0.0f;
@@ -337,7 +354,7 @@ template <typename T>
 __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
     const T* __restrict__ x, const float* __restrict__ logits, const int* __restrict__ topk_idx,
     const int* __restrict__ slot, const float* __restrict__ dw, const float* __restrict__ dw_part, int parts,
-    float* __restrict__ dL, float* __restrict__ part, int t_begin, int t_count, int M, int E, int k) {
+    float* __restrict__ dL, float* __restrict__ part, int t_begin, int t_count, int M, int E, int k, int renorm) {
     // dL of the block's tokens; rows of missing tokens and columns from E up to the next
     // multiple of 16 stay zero, so the product loop below needs no predicates
     __shared__ __attribute__((aligned(16))) float sdl[DWG_TOK][DWG_EMAX + 4];
@@ -384,7 +401,7 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
     }
     __syncthreads();
     if ((int)threadIdx.x < nt)
-        gate_dl_token(logits, topk_idx, sdw + threadIdx.x * k, dL, sdl[threadIdx.x], t_begin + tl0 + threadIdx.x, E, k);
+        gate_dl_token(logits, topk_idx, sdw + threadIdx.x * k, dL, sdl[threadIdx.x], t_begin + tl0 + threadIdx.x, E, k, renorm);
     __syncthreads();
     for (int c = threadIdx.x * 8; c < M; c += PERM_THREADS * 8) {
         for (int e0 = 0; e0 < E; e0 += 16) {
@@ -517,7 +534,7 @@ static moe_status gate_bwd_t(const Dims& d, int part, const void* x, const float
     ProfScope ps(PK_GATE_BWD, s);
     const int nblk = (d.Tp + DWG_TOK - 1) / DWG_TOK;
     hipLaunchKernelGGL((gate_bwd_kernel<T>), dim3(1, nblk), dim3(PERM_THREADS), 0, s, (const T*)x, logits, idx,
-                       slot, dw, dw_part, parts, dL, (float*)scratch, part * d.Tp, d.Tp, d.M, d.E, d.k);
+                       slot, dw, dw_part, parts, dL, (float*)scratch, part * d.Tp, d.Tp, d.M, d.E, d.k, d.renorm);
     MOE_CHECK_LAUNCH();
     const int ME = d.M * d.E;
     hipLaunchKernelGGL(gate_dwg_reduce_kernel, dim3((ME + 31) / 32), dim3(256), 0, s,

@@ -43,7 +43,7 @@ constexpr int ROUTE_THREADS = 512;
 constexpr int ROUTE_WAVES = ROUTE_THREADS / 64;
 
 // softmax over E logits and the k largest of them; runs in one lane per token
-__device__ __forceinline__ void softmax_topk(const float* lg, int E, int k, int* idx_out, float* w_out) {
+__device__ __forceinline__ void softmax_topk(const float* lg, int E, int k, int renorm, int* idx_out, float* w_out) {
     float mx = -INFINITY;
     for (int e = 0; e < E; ++e) mx = fmaxf(mx, lg[e]);
     float sum = 0.0f;
@@ -60,8 +60,15 @@ __device__ __forceinline__ void softmax_topk(const float* lg, int E, int k, int*
         }
         taken |= 1ull << best;
         idx_out[j] = best;
-        w_out[j] = expf(lg[best] - mx) / sum;
+        w_out[j] = expf(lg[best] - mx);
     }
+    // weights: the chosen probabilities, or those divided by their sum over the k choices
+    float den = sum;
+    if (renorm) {
+        den = 0.0f;
+        for (int j = 0; j < k; ++j) den += w_out[j];
+    }
+    for (int j = 0; j < k; ++j) w_out[j] = w_out[j] / den;
 }
 
 // EP = E rounded up to a power of two (>= 4); TB tokens per wavefront, TB*EP <= 64.
@@ -70,7 +77,7 @@ template <typename T, int EP, int TB>
 __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
     const T* __restrict__ x, const T* __restrict__ Wg, const float* __restrict__ bias,
     float* __restrict__ logits, int* __restrict__ topk_idx, float* __restrict__ topk_w,
-    int Ttot, int M, int E, int k, int MC) {
+    int Ttot, int M, int E, int k, int MC, int renorm) {
     extern __shared__ float smem[];
     float* wl = smem;                               // [MC/8 ... ] see index below
     float* lg = smem + (size_t)MC * EP;             // [ROUTE_WAVES][TB][EP]
@@ -178,7 +185,7 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
             for (int e = 0; e < E; ++e) logits[(size_t)t * E + e] = my[e];
             int ids[8];
             float ws[8];
-            softmax_topk(my, E, k, ids, ws);
+            softmax_topk(my, E, k, renorm, ids, ws);
             for (int j = 0; j < k; ++j) {
                 topk_idx[(size_t)t * k + j] = ids[j];
                 topk_w[(size_t)t * k + j] = ws[j];
@@ -209,7 +216,7 @@ static moe_status launch_route(const Dims& d, const void* x, const void* Wg, con
     int grid = ngroups < cap ? ngroups : cap;
     ProfScope ps(PK_ROUTE, s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(ROUTE_THREADS), lds, s,
-                       (const T*)x, (const T*)Wg, bias, logits, idx, w, d.T, d.M, d.E, d.k, MC);
+                       (const T*)x, (const T*)Wg, bias, logits, idx, w, d.T, d.M, d.E, d.k, MC, d.renorm);
     count_launch(LC_OTHER);
     MOE_CHECK_LAUNCH();
     return MOE_OK;

@@ -124,6 +124,28 @@ def test_edge_cases_full_parity(oracle, runner, case, mode):
         assert (r["counts"] == 0).any(), "case is meant to leave some expert without rows"
 
 
+@pytest.mark.parametrize("case,mode", [("small", 2), ("small", 0), ("tiny", 0), ("k3", 2)])
+def test_renormalised_gate_variant(oracle, runner, case, mode):
+    """Combine weights divided by their sum over the token's k choices (gate_renormalize)."""
+    if case == "k3":
+        s, n = synth.custom_shape(328, 264, 328, 6, 3, 0.9, dtype="bf16", x_std=1.0, w_std=0.05, name="k3"), 2
+    else:
+        s, n = synth.WORKLOADS[case], (2 if case == "small" else 1)
+    d = synth.make_inputs(s, seed=6)
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], s.k, s.capacity_factor, n,
+                          gate_bias=d.get("gate_bias"), renormalize=True)
+    g = runner.run_layer_step(s, d, n, mode, gate_renormalize=1)
+    _check_routing(g, r)
+    if s.k > 1:
+        _check_values(g, r, TOL[s.dtype])
+        assert np.abs(g["w"].sum(axis=1) - 1.0).max() <= 1e-6
+    else:
+        # one choice: its weight is exactly 1 and the gate gets no gradient at all
+        _check_values(g, r, TOL[s.dtype], names=("y", "dx", "dW1", "dW2"))
+        assert np.all(g["w"] == 1.0)
+        assert np.abs(g["dWg"]).max() <= 1e-6 * np.abs(g["dW1"]).max()
+
+
 def test_results_do_not_depend_on_streams_or_reuse_mode(runner):
     """Same kernels, same order of accumulation: one stream or two, and the three
     memory modes, give identical routing and values that agree to rounding."""
