@@ -53,8 +53,16 @@ typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
  *             re-dispatched from T_I in backward; T_M is kept whole.
  *   RECOMPUTE as BUFFERS, and T_M lives in one partition-sized buffer and is
  *             recomputed from T_DI in backward (strategy S4 with the
- *             re-communication read as a local re-dispatch). */
-typedef enum { MOE_REUSE_NONE = 0, MOE_REUSE_BUFFERS = 1, MOE_REUSE_RECOMPUTE = 2 } moe_reuse;
+ *             re-communication read as a local re-dispatch).
+ *   S1, S2, S3  the offloading strategies of Table II, for moe_layer_step_offload
+ *             only: shared T_DI/T_DO buffers as in BUFFERS, and in forward T_DI (S1,
+ *             S3) and/or T_M (S1, S2) of every partition are copied to pinned host
+ *             memory on a third stream and copied back before the partition's
+ *             backward GEMMs; S2 re-dispatches T_DI, S3 recomputes T_M.  T_M then
+ *             lives in two partition-sized buffers (one being copied while the next
+ *             is written), one for S3. */
+typedef enum { MOE_REUSE_NONE = 0, MOE_REUSE_BUFFERS = 1, MOE_REUSE_RECOMPUTE = 2,
+               MOE_REUSE_S1 = 3, MOE_REUSE_S2 = 4, MOE_REUSE_S3 = 5 } moe_reuse;
 
 typedef struct {
     int32_t T, M, H, E, k;
@@ -181,6 +189,21 @@ moe_status moe_layer_step(const moe_config* cfg, const void* x, const void* dy,
                           float* logits, int32_t* topk_idx, float* topk_w, int32_t* slot, int32_t* counts,
                           void* workspace, size_t workspace_bytes,
                           void* const* streams, int32_t n_streams);
+
+/* moe_layer_step for the offloading strategies (cfg->reuse = MOE_REUSE_S1..S3; Section
+ * III-D, Table II).  host_buffer: pinned host memory (hipHostMalloc) of at least
+ * moe_offload_bytes(cfg) bytes, owned by the caller, overwritten by every call.
+ * streams: at least 3 (permutations, GEMMs, copies); joins back to streams[0].
+ * The copies are hipMemcpyAsync calls: not for use under stream capture.
+ * The other entry points reject these modes with MOE_ERR_UNSUPPORTED. */
+moe_status moe_offload_bytes(const moe_config* cfg, size_t* host_bytes);
+moe_status moe_layer_step_offload(const moe_config* cfg, const void* x, const void* dy,
+                                  const void* Wg, const float* gate_bias, const void* W1, const void* W2,
+                                  void* y, void* dx, float* dWg, float* dW1, float* dW2,
+                                  float* logits, int32_t* topk_idx, float* topk_w, int32_t* slot, int32_t* counts,
+                                  void* workspace, size_t workspace_bytes,
+                                  void* host_buffer, size_t host_bytes,
+                                  void* const* streams, int32_t n_streams);
 
 /* Forward half / backward half of moe_layer_step, for callers that run other
  * work between them.  Same arguments and workspace; backward reads what forward

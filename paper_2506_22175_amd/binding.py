@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_REUSE_NONE, MOE_REUSE_BUFFERS, MOE_REUSE_RECOMPUTE = 0, 1, 2
+MOE_REUSE_S1, MOE_REUSE_S2, MOE_REUSE_S3 = 3, 4, 5
 
 EXPORTS = [
     "moe_capacity", "moe_workspace_bytes", "moe_route", "moe_assign_slots", "moe_slot_scratch_bytes",
@@ -26,6 +27,7 @@ EXPORTS = [
     "moe_last_error", "moe_profile_enable", "moe_profile_read",
     "moe_gran_create", "moe_gran_destroy", "moe_gran_lookup", "moe_gran_record", "moe_gran_ranges",
     "moe_search_best_gran", "moe_gran_get", "moe_strategy_cost", "moe_select_strategy",
+    "moe_offload_bytes", "moe_layer_step_offload",
 ]
 
 
@@ -332,3 +334,23 @@ def moe_select_strategy(allowed_mask: int, b: int, M: int, H: int, speeds: MoESp
                                      ctypes.c_int64(H), ctypes.byref(speeds), ctypes.byref(best), ctypes.byref(cost)),
            "moe_select_strategy")
     return best.value, cost.value
+
+
+# ---- offloading strategies ---------------------------------------------------------------
+
+def moe_offload_bytes(cfg: MoEConfig) -> int:
+    v = ctypes.c_size_t(0)
+    _check(lib().moe_offload_bytes(_cfg(cfg), ctypes.byref(v)), "moe_offload_bytes")
+    return v.value
+
+
+def moe_layer_step_offload(cfg, x, dy, Wg, gate_bias, W1, W2, y, dx, dWg, dW1, dW2, logits, topk_idx, topk_w, slot,
+                           counts, workspace, host_buffer, streams):
+    """host_buffer: pinned host tensor (uint8); streams: three streams."""
+    arr, n = _streams(streams)
+    _check(lib().moe_layer_step_offload(_cfg(cfg), _p(x), _p(dy), _p(Wg), _p(gate_bias), _p(W1), _p(W2), _p(y),
+                                        _p(dx), _p(dWg), _p(dW1), _p(dW2), _p(logits), _p(topk_idx), _p(topk_w),
+                                        _p(slot), _p(counts), _p(workspace),
+                                        ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+                                        _p(host_buffer), ctypes.c_size_t(host_buffer.numel() * host_buffer.element_size()),
+                                        arr, n), "moe_layer_step_offload")

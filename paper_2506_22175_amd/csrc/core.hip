@@ -14,7 +14,7 @@ moe_status make_dims(const moe_config* cfg, Dims* d) {
     if (!(cfg->capacity_factor > 0.0f) || !std::isfinite(cfg->capacity_factor)) return MOE_ERR_SHAPE;
     if (cfg->n_partitions <= 0 || cfg->T % cfg->n_partitions != 0) return MOE_ERR_SHAPE;
     if (cfg->dtype != MOE_F32 && cfg->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
-    if (cfg->reuse < MOE_REUSE_NONE || cfg->reuse > MOE_REUSE_RECOMPUTE) return MOE_ERR_UNSUPPORTED;
+    if (cfg->reuse < MOE_REUSE_NONE || cfg->reuse > MOE_REUSE_S3) return MOE_ERR_UNSUPPORTED;
     if (cfg->E > 64 || cfg->k > 8 || cfg->n_partitions > 64) return MOE_ERR_UNSUPPORTED;
     if (cfg->M % 8 != 0 || cfg->H % 8 != 0) return MOE_ERR_UNSUPPORTED;
     d->T = cfg->T; d->M = cfg->M; d->H = cfg->H; d->E = cfg->E; d->k = cfg->k;

@@ -34,13 +34,26 @@ struct Workspace {
     size_t total, saved, temp, routing;
 };
 
+// What each mode does with the two tensors that backward needs again (Table II).
+static bool mode_recomputes(int reuse) { return reuse == MOE_REUSE_RECOMPUTE || reuse == MOE_REUSE_S3; }
+static bool mode_offloads_di(int reuse) { return reuse == MOE_REUSE_S1 || reuse == MOE_REUSE_S3; }
+static bool mode_offloads_z(int reuse) { return reuse == MOE_REUSE_S1 || reuse == MOE_REUSE_S2; }
+static bool mode_offloads(int reuse) { return mode_offloads_di(reuse) || mode_offloads_z(reuse); }
+
+// Host side of the offloading strategies: where each partition's copy lives, and the copy stream.
+struct Offload {
+    char* host = nullptr;
+    size_t DI = 0, Z = 0;        // offsets in host; n buffers each (when offloaded)
+    hipStream_t s2 = nullptr;
+};
+
 static moe_status plan(const moe_config* cfg, const Dims& d, Workspace* w) {
     w->bufM = align_up((size_t)d.Rp * d.M * d.es);
     w->bufH = align_up((size_t)d.Rp * d.H * d.es);
     const bool reuse = d.reuse != MOE_REUSE_NONE;
     w->nDI = (reuse && d.n > 2) ? 2 : d.n;
     w->nDO = (reuse && d.n > 2) ? 2 : d.n;
-    w->nZ = d.reuse == MOE_REUSE_RECOMPUTE ? 1 : d.n;
+    w->nZ = mode_recomputes(d.reuse) ? 1 : mode_offloads_z(d.reuse) ? (d.n < 2 ? d.n : 2) : d.n;
     w->dDO_aliases_DO = reuse;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
@@ -84,13 +97,17 @@ static moe_status get_events(size_t n) {
 static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace& w, char* ws,
                           const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* W2,
                           void* y, float* logits, int* topk_idx, float* topk_w, int* slot, int* counts,
-                          hipStream_t s0, hipStream_t s1) {
+                          hipStream_t s0, hipStream_t s1, const Offload* off = nullptr) {
     const int n = d.n;
-    MOE_TRY(get_events(3 * (size_t)n + 1));
+    MOE_TRY(get_events(6 * (size_t)n + 2));
     hipEvent_t* evS = g_events.data();
     hipEvent_t* evC = evS + n;
     hipEvent_t* evR = evC + n;
-    hipEvent_t evFork = g_events[3 * (size_t)n];
+    hipEvent_t* evDIout = evR + n;            // T_DI of p is on the host
+    hipEvent_t* evZout = evDIout + n;         // T_M of p is on the host
+    hipEvent_t evFork = g_events[6 * (size_t)n];
+    hipEvent_t evCopies = g_events[6 * (size_t)n + 1];
+    const bool off_di = off && mode_offloads_di(d.reuse), off_z = off && mode_offloads_z(d.reuse);
 
     MOE_TRY(moe_route(cfg, x, Wg, gate_bias, logits, topk_idx, topk_w, s0));
     MOE_TRY(moe_assign_slots(cfg, topk_idx, topk_w, slot, counts, (float*)(ws + w.slot_w),
@@ -101,22 +118,34 @@ static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace&
     auto DIbuf = [&](int p) { return ws + w.DI + w.bufM * (p % w.nDI); };
     auto DObuf = [&](int p) { return ws + w.DO + w.bufM * (p % w.nDO); };
     auto Zbuf = [&](int p) { return ws + w.Z + w.bufH * (p % w.nZ); };
-    const bool keepZ = d.reuse != MOE_REUSE_RECOMPUTE;
+    const bool keepZ = !mode_recomputes(d.reuse);
 
     for (int p = 0; p <= n; ++p) {
         if (p < n) {
             // S_p.  A shared T_DI buffer was last read by C_{p-2}; R_{p-2}, already
-            // queued on this stream, waited for C_{p-2}.
+            // queued on this stream, waited for C_{p-2}.  Its copy to the host must be through too.
+            if (off_di && p >= w.nDI) HIP_TRY(hipStreamWaitEvent(s0, evDIout[p - w.nDI], 0));
             MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
             HIP_TRY(hipEventRecord(evS[p], s0));
+            if (off_di) {
+                HIP_TRY(hipStreamWaitEvent(off->s2, evS[p], 0));
+                HIP_TRY(hipMemcpyAsync(off->host + off->DI + w.bufM * p, DIbuf(p), w.bufM, hipMemcpyDeviceToHost, off->s2));
+                HIP_TRY(hipEventRecord(evDIout[p], off->s2));
+            }
             // C_p
             HIP_TRY(hipStreamWaitEvent(s1, evS[p], 0));
             if (p >= w.nDO) HIP_TRY(hipStreamWaitEvent(s1, evR[p - w.nDO], 0));   // T_DO buffer free again
+            if (off_z && p >= w.nZ) HIP_TRY(hipStreamWaitEvent(s1, evZout[p - w.nZ], 0));   // T_M buffer copied out
             // with recomputation T_M is not kept: the activated rows go to the one
             // shared H-wide buffer and the pre-activation is not written at all
             void* Aout = keepZ ? (void*)(ws + w.HT) : (void*)Zbuf(p);
             MOE_TRY(ffn_fwd(d, p, DIbuf(p), counts, W1, W2, keepZ ? Zbuf(p) : nullptr, Aout, DObuf(p), s1));
             HIP_TRY(hipEventRecord(evC[p], s1));
+            if (off_z) {
+                HIP_TRY(hipStreamWaitEvent(off->s2, evC[p], 0));
+                HIP_TRY(hipMemcpyAsync(off->host + off->Z + w.bufH * p, Zbuf(p), w.bufH, hipMemcpyDeviceToHost, off->s2));
+                HIP_TRY(hipEventRecord(evZout[p], off->s2));
+            }
         }
         if (p >= 1) {
             // R_{p-1}, issued after S_p so that S and R alternate on stream 0
@@ -125,6 +154,10 @@ static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace&
             HIP_TRY(hipEventRecord(evR[p - 1], s0));
         }
     }
+    if (off_di || off_z) {                       // the host copies belong to what stream 0 has finished
+        HIP_TRY(hipEventRecord(evCopies, off->s2));
+        HIP_TRY(hipStreamWaitEvent(s0, evCopies, 0));
+    }
     return MOE_OK;
 }
 
@@ -132,15 +165,17 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
                            const void* x, const void* dy, const void* Wg, const void* W1, const void* W2,
                            void* dx, float* dWg, float* dW1, float* dW2,
                            const float* logits, const int* topk_idx, const int* slot, const int* counts,
-                           hipStream_t s0, hipStream_t s1) {
+                           hipStream_t s0, hipStream_t s1, const Offload* off = nullptr) {
     const int n = d.n;
-    MOE_TRY(get_events(3 * (size_t)n + 1));
+    MOE_TRY(get_events(6 * (size_t)n + 2));
     hipEvent_t* evS = g_events.data();        // R'_p done (rows of dy, and of x again, are in place)
     hipEvent_t* evC = evS + n;                // backward GEMMs of p done
     hipEvent_t* evD = evC + n;                // S'_p done (dDI and dw_part of p consumed)
-    hipEvent_t evFork = g_events[3 * (size_t)n];
+    hipEvent_t* evIn = evD + n;               // T_DI / T_M of p are back from the host
+    hipEvent_t evFork = g_events[6 * (size_t)n];
     const bool reuse = d.reuse != MOE_REUSE_NONE;
-    const bool recompute = d.reuse == MOE_REUSE_RECOMPUTE;
+    const bool recompute = mode_recomputes(d.reuse);
+    const bool off_di = off && mode_offloads_di(d.reuse), off_z = off && mode_offloads_z(d.reuse);
 
     auto DIbuf = [&](int p) { return ws + w.DI + w.bufM * (p % w.nDI); };
     auto DObuf = [&](int p) { return ws + w.DO + w.bufM * (p % w.nDO); };
@@ -154,6 +189,8 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
 
     HIP_TRY(hipEventRecord(evFork, s0));
     HIP_TRY(hipStreamWaitEvent(s1, evFork, 0));
+    // copies back into the shared buffers must not overtake the forward GEMMs that still read them
+    if (off_di || off_z) HIP_TRY(hipStreamWaitEvent(off->s2, evFork, 0));
 
     for (int p = 0; p <= n; ++p) {
         if (p < n) {
@@ -162,12 +199,23 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
             if (p >= 2) HIP_TRY(hipStreamWaitEvent(s0, evC[p - 2], 0));
             if (reuse) {
                 MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), nullptr, nullptr, s0));
-                MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));   // T_DI from T_I again
+                if (!off_di) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));   // T_DI from T_I again
             } else {
                 // T_DO was kept: the combine-weight gradient is <dy_t, T_DO row>
                 MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), DObuf(p), dw, s0));
             }
             HIP_TRY(hipEventRecord(evS[p], s0));
+            if (off_di || off_z) {
+                // what was offloaded comes back into the shared buffers, last read by the GEMMs of p-2
+                // (the copy stream runs in order, so the forward copies are through)
+                if (p >= 2) HIP_TRY(hipStreamWaitEvent(off->s2, evC[p - 2], 0));
+                if (off_di)
+                    HIP_TRY(hipMemcpyAsync(DIbuf(p), off->host + off->DI + w.bufM * p, w.bufM, hipMemcpyHostToDevice, off->s2));
+                if (off_z)
+                    HIP_TRY(hipMemcpyAsync(Zbuf(p), off->host + off->Z + w.bufH * p, w.bufH, hipMemcpyHostToDevice, off->s2));
+                HIP_TRY(hipEventRecord(evIn[p], off->s2));
+                HIP_TRY(hipStreamWaitEvent(s1, evIn[p], 0));
+            }
             // C'_p
             HIP_TRY(hipStreamWaitEvent(s1, evS[p], 0));
             if (p >= 2) HIP_TRY(hipStreamWaitEvent(s1, evD[p - 2], 0));
@@ -189,10 +237,12 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
 }
 
 static moe_status setup(const moe_config* cfg, Dims* d, Workspace* w, void* workspace, size_t workspace_bytes,
-                        void* const* streams, int n_streams, hipStream_t* s0, hipStream_t* s1) {
+                        void* const* streams, int n_streams, hipStream_t* s0, hipStream_t* s1,
+                        bool with_host = false) {
     MOE_TRY(make_dims(cfg, d));
     if (!workspace || !streams) return MOE_ERR_NULL;
     if (n_streams < 2) return MOE_ERR_SHAPE;
+    if (mode_offloads(d->reuse) != with_host) return MOE_ERR_UNSUPPORTED;
     MOE_TRY(plan(cfg, *d, w));
     if (workspace_bytes < w->total) return MOE_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_WORKSPACE;
@@ -260,4 +310,54 @@ extern "C" moe_status moe_layer_step(const moe_config* cfg, const void* x, const
                     counts, s0, s1));
     return backward(cfg, d, w, (char*)workspace, x, dy, Wg, W1, W2, dx, dWg, dW1, dW2, logits, topk_idx, slot,
                     counts, s0, s1);
+}
+
+static void offload_layout(const Dims& d, const Workspace& w, Offload* o, size_t* total) {
+    size_t off = 0;
+    o->DI = off;
+    if (mode_offloads_di(d.reuse)) off += w.bufM * (size_t)d.n;
+    o->Z = off;
+    if (mode_offloads_z(d.reuse)) off += w.bufH * (size_t)d.n;
+    *total = off;
+}
+
+extern "C" moe_status moe_offload_bytes(const moe_config* cfg, size_t* host_bytes) {
+    Dims d;
+    MOE_TRY(make_dims(cfg, &d));
+    if (!host_bytes) return MOE_ERR_NULL;
+    if (!mode_offloads(d.reuse)) return MOE_ERR_UNSUPPORTED;
+    Workspace w;
+    MOE_TRY(plan(cfg, d, &w));
+    Offload o;
+    offload_layout(d, w, &o, host_bytes);
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_layer_step_offload(const moe_config* cfg, const void* x, const void* dy,
+                                             const void* Wg, const float* gate_bias, const void* W1, const void* W2,
+                                             void* y, void* dx, float* dWg, float* dW1, float* dW2,
+                                             float* logits, int32_t* topk_idx, float* topk_w, int32_t* slot,
+                                             int32_t* counts, void* workspace, size_t workspace_bytes,
+                                             void* host_buffer, size_t host_bytes,
+                                             void* const* streams, int32_t n_streams) {
+    Dims d; Workspace w; hipStream_t s0, s1;
+    if (n_streams < 3) return streams ? MOE_ERR_SHAPE : MOE_ERR_NULL;
+    MOE_TRY(setup(cfg, &d, &w, workspace, workspace_bytes, streams, n_streams, &s0, &s1, true));
+    if (!x || !dy || !Wg || !W1 || !W2 || !y || !dx || !dWg || !dW1 || !dW2 || !logits || !topk_idx ||
+        !topk_w || !slot || !counts || !host_buffer) return MOE_ERR_NULL;
+    Offload o;
+    size_t need = 0;
+    offload_layout(d, w, &o, &need);
+    if (host_bytes < need) return MOE_ERR_WORKSPACE;
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, host_buffer) != hipSuccess || attr.type != hipMemoryTypeHost) {
+        (void)hipGetLastError();
+        return MOE_ERR_UNSUPPORTED;               // pageable memory would make the copies synchronous
+    }
+    o.host = (char*)host_buffer;
+    o.s2 = (hipStream_t)streams[2];
+    MOE_TRY(forward(cfg, d, w, (char*)workspace, x, Wg, gate_bias, W1, W2, y, logits, topk_idx, topk_w, slot,
+                    counts, s0, s1, &o));
+    return backward(cfg, d, w, (char*)workspace, x, dy, Wg, W1, W2, dx, dWg, dW1, dW2, logits, topk_idx, slot,
+                    counts, s0, s1, &o);
 }

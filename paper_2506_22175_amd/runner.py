@@ -59,6 +59,12 @@ class LayerState:
         self.workspace = torch.empty((ws_alloc,), dtype=torch.uint8, device=dev)
         self.s0 = torch.cuda.current_stream(dev)
         self.s1 = torch.cuda.Stream(dev) if second_stream else self.s0
+        # offloading strategies: pinned host buffer and a third stream for the copies
+        self.host_buffer = None
+        self.s2 = None
+        if reuse >= B.MOE_REUSE_S1:
+            self.host_buffer = torch.empty((max(B.moe_offload_bytes(self.cfg), 1),), dtype=torch.uint8, pin_memory=True)
+            self.s2 = torch.cuda.Stream(dev) if second_stream else self.s0
         self.inputs: Dict[str, Optional[torch.Tensor]] = {}
 
     def upload(self, inp: Dict[str, np.ndarray]):
@@ -75,6 +81,8 @@ class LayerState:
     def poison(self):
         """Fill everything the step must overwrite with NaN / -2 so stale data shows."""
         self.workspace.fill_(0xFF)          # 0xFFFF bf16 and 0xFFFFFFFF float are NaN
+        if self.host_buffer is not None:
+            self.host_buffer.fill_(0xFF)
         for t in (self.y, self.dx, self.logits, self.topk_w):
             t.fill_(float("nan"))
         self.topk_idx.fill_(-2)
@@ -83,6 +91,12 @@ class LayerState:
 
     def step(self):
         i = self.inputs
+        if self.host_buffer is not None:
+            B.moe_layer_step_offload(self.cfg, i["x"], i["dy"], i["Wg"], i["gate_bias"], i["W1"], i["W2"], self.y,
+                                     self.dx, self.dWg, self.dW1, self.dW2, self.logits, self.topk_idx, self.topk_w,
+                                     self.slot, self.counts, self.workspace, self.host_buffer,
+                                     [self.s0, self.s1, self.s2])
+            return
         B.moe_layer_step(self.cfg, i["x"], i["dy"], i["Wg"], i["gate_bias"], i["W1"], i["W2"], self.y, self.dx,
                          self.dWg, self.dW1, self.dW2, self.logits, self.topk_idx, self.topk_w, self.slot,
                          self.counts, self.workspace, [self.s0, self.s1])

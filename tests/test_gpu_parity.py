@@ -146,6 +146,52 @@ def test_renormalised_gate_variant(oracle, runner, case, mode):
         assert np.abs(g["dWg"]).max() <= 1e-6 * np.abs(g["dW1"]).max()
 
 
+@pytest.mark.parametrize("mode", [3, 4, 5])
+@pytest.mark.parametrize("n", [1, 2, 4])
+def test_offloading_strategies_give_the_same_step(oracle, runner, mode, n):
+    """S1, S2, S3 of Table II: T_DI and/or T_M travel to pinned host memory in forward and back in
+    backward on a third stream.  Copies change no value: S1/S2 equal mode 1 bit for bit (T_M kept,
+    here on the host), S3 equals mode 2 (T_M recomputed); and the oracle agrees as for any mode."""
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=7)
+    g = runner.run_layer_step(s, d, n, mode)
+    same = runner.run_layer_step(s, d, n, 2 if mode == 5 else 1)
+    for k_ in ("y", "dx", "dWg", "dW1", "dW2", "idx", "slot", "counts", "w"):
+        assert np.array_equal(g[k_], same[k_]), k_
+    r = _oracle(oracle, s, d, n)
+    _check_routing(g, r)
+    _check_values(g, r, TOL[s.dtype])
+
+
+def test_offloading_needs_its_own_entry_point_and_pinned_memory(runner):
+    import torch
+    from paper_2506_22175_amd import binding as B
+    s = synth.WORKLOADS["tiny"]
+    d = synth.make_inputs(s, seed=0)
+    st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, 1, s.dtype, 3)
+    st.upload(d)
+    i = st.inputs
+    args = (st.cfg, i["x"], i["dy"], i["Wg"], i["gate_bias"], i["W1"], i["W2"], st.y, st.dx, st.dWg, st.dW1, st.dW2,
+            st.logits, st.topk_idx, st.topk_w, st.slot, st.counts, st.workspace)
+    with pytest.raises(B.MoEError) as e:                      # the plain entry point refuses the mode
+        B.moe_layer_step(*args, [st.s0, st.s1])
+    assert e.value.status == 3
+    pageable = torch.empty((B.moe_offload_bytes(st.cfg),), dtype=torch.uint8)
+    with pytest.raises(B.MoEError) as e:
+        B.moe_layer_step_offload(*args, pageable, [st.s0, st.s1, st.s2])
+    assert e.value.status == 3
+    with pytest.raises(B.MoEError) as e:                      # two streams are not enough
+        B.moe_layer_step_offload(*args, st.host_buffer, [st.s0, st.s1])
+    assert e.value.status == 2
+    small = torch.empty((16,), dtype=torch.uint8, pin_memory=True)
+    with pytest.raises(B.MoEError) as e:
+        B.moe_layer_step_offload(*args, small, [st.s0, st.s1, st.s2])
+    assert e.value.status == 4
+    st.step()                                                 # and the right call works
+    torch.cuda.synchronize()
+    assert np.isfinite(runner.to_host(st.y)).all()
+
+
 def test_results_do_not_depend_on_streams_or_reuse_mode(runner):
     """Same kernels, same order of accumulation: one stream or two, and the three
     memory modes, give identical routing and values that agree to rounding."""
