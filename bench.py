@@ -192,19 +192,42 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
                 fw, bw = B.moe_strategy_cost(num, int(round(rows_pp)), M, H, sp)
                 model[name] = {"fw_ms_per_microbatch": fw * 1e3, "bw_ms_per_microbatch": bw * 1e3,
                                "step_ms": n * (fw + bw) * 1e3}
+            # host copies: elements of the storage type per second over PCIe, measured alone
+            hb = torch.empty((256 << 20,), dtype=torch.uint8, pin_memory=True)
+            db = torch.empty((256 << 20,), dtype=torch.uint8, device=st.device)
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            hb.copy_(db, non_blocking=True)
+            torch.cuda.synchronize()
+            c0.record()
+            hb.copy_(db, non_blocking=True)
+            db.copy_(hb, non_blocking=True)
+            c1.record()
+            torch.cuda.synchronize()
+            sp.W_mem = 2.0 * (256 << 20) / es / (c0.elapsed_time(c1) * 1e-3)
+            sp.mu_all = sp.mu_comp
+            del hb, db
+            for name, num in (("S1", 1), ("S2", 2), ("S3", 3)):
+                fw, bw = B.moe_strategy_cost(num, int(round(rows_pp)), M, H, sp)
+                model[name] = {"fw_ms_per_microbatch": fw * 1e3, "bw_ms_per_microbatch": bw * 1e3,
+                               "step_ms": n * (fw + bw) * 1e3}
             pick, _ = B.moe_select_strategy(0b10001, int(round(rows_pp)), M, H, sp)
+            pick_all, _ = B.moe_select_strategy(0b11110, int(round(rows_pp)), M, H, sp)
             cost_model = {"W_comp_TMAC_per_s": sp.W_comp / 1e12, "W_comm_Gelem_per_s": sp.W_comm / 1e9,
                           "sigma_comp_beside_permutations": sp.sigma, "mu_permutations_beside_comp": sp.mu_comp,
+                          "W_mem_Gelem_per_s": sp.W_mem / 1e9,
                           "eq10": model, "cheapest_of_none_and_S4": B.STRATEGIES[pick],
+                          "cheapest_memory_saving_strategy": B.STRATEGIES[pick_all],
                           "this_run": {"strategy": {0: "none", 2: "S4"}.get(reuse, "mode 1 (no row in Table II)"),
                                        "measured_step_ms": ms_per_step}}
 
     mem = {}
-    for mode in (0, 1, 2):
+    for mode in (0, 1, 2, 3, 4, 5):
         cfg = B.make_config(T, M, H, shape.E, k, shape.capacity_factor, n,
                             B.MOE_BF16 if shape.dtype == "bf16" else B.MOE_F32, mode)
         total, saved, temp, routing = B.moe_workspace_bytes(cfg)
         mem[f"mode{mode}"] = {"workspace": total, "saved_activations": saved, "temporaries": temp, "routing": routing}
+        if mode >= 3:
+            mem[f"mode{mode}"]["pinned_host"] = B.moe_offload_bytes(cfg)
     mem["max_memory_allocated_this_run"] = int(peak_alloc)
 
     out = {
@@ -296,12 +319,22 @@ def main():
         # the other workloads of the set, a few steps each, for the record
         others = []
         for wl, n, mode in (("small", 1, 2), ("gpt", 1, 2), ("gpt", 4, 2), ("skewed", 4, 2), ("large", 4, 2),
-                            ("large", 8, 2), (args.workload, args.n, 0), (args.workload, args.n, 1)):
+                            ("large", 8, 2), (args.workload, args.n, 0), (args.workload, args.n, 1),
+                            (args.workload, args.n, 3), (args.workload, args.n, 4), (args.workload, args.n, 5)):
             if wl == args.workload and n == args.n and mode == args.reuse:
                 continue
             o, _, _ = measure(args, wl, n, mode, 5, 2, brief=True)
             others.append(o)
         out["other_workloads"] = others
+        # measured step of every strategy of Table II beside Eq. 10's prediction
+        names = {0: "none", 2: "S4", 3: "S1", 4: "S2", 5: "S3"}
+        eq10 = out.get("interference_and_cost_model", {}).get("eq10", {})
+        meas = {names[o["reuse_mode"]]: o["ms_per_step"] for o in others
+                if o["workload"] == out["config"]["workload"] and o["n_partitions"] == args.n and o["reuse_mode"] in names}
+        meas[names.get(args.reuse, "mode 1")] = out["ms_per_step"]
+        if eq10:
+            out["interference_and_cost_model"]["measured_vs_eq10_step_ms"] = {
+                k_: {"measured": meas.get(k_), "eq10": v["step_ms"]} for k_, v in eq10.items()}
     if not args.no_sweep:
         out["adaptive_granularity"] = granularity_report(args, shape, inp, args.reuse)
     if not args.no_cpu_baseline:
