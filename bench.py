@@ -84,7 +84,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
     if graph is not None:
         for _ in range(2):
             run_step()
-    B.moe_profile_enable(graph is None)
+    B.moe_profile_enable(graph is None and not args.no_kernel_timing)
     ev0 = torch.cuda.Event(enable_timing=True)
     ev1 = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -142,7 +142,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
                 "kernel_timing": kernel_timing}
 
     # HBM-bound permutations: algorithmic bytes = rows read + rows written
-    n_disp_per_step = 1 + (2 if reuse else 1)          # x forward; dy (+ x again) backward
+    n_disp_per_step = 1 + (2 if (reuse in (1, 2, 4) and n > 2) else 1)   # x forward; dy (+ x again when T_DI buffers are shared) backward
     bytes_dispatch = 2.0 * R * M * es                       # per dispatch of all partitions
     bytes_combine = (R + T) * M * es + T * k * 8.0
     bytes_dbwd = (R + T) * M * es + T * shape.E * 4.0
@@ -314,6 +314,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="replay a captured HIP graph of the step (no per-kernel timing)")
     ap.add_argument("--accumulate", action="store_true",
                     help="weight gradients are added to the buffers (default: each step overwrites them)")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="no HIP events around the kernels in the timed region (roofline fields are then empty)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the short runs of the other workloads")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -199,7 +199,9 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
             if (p >= 2) HIP_TRY(hipStreamWaitEvent(s0, evC[p - 2], 0));
             if (reuse) {
                 MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), nullptr, nullptr, s0));
-                if (!off_di) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));   // T_DI from T_I again
+                // T_DI from T_I again - unless every partition still has its own buffer (n <= 2 shares
+                // nothing), which then holds what forward put there
+                if (!off_di && w.nDI < n) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
             } else {
                 // T_DO was kept: the combine-weight gradient is <dy_t, T_DO row>
                 MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), DObuf(p), dw, s0));

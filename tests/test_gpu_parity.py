@@ -404,7 +404,9 @@ def test_kernel_timing_hooks_see_every_gemm(runner):
     B.moe_profile_enable(False)
     prof = B.moe_profile_read()
     assert prof["gemm_fwd1_gelu"][0] == 2 and prof["gemm_nn_store"][0] == 4 and prof["gemm_wgrad"][0] == 4
-    assert prof["gemm_dgelu"][0] == 2 and prof["gemm_dgrad"][0] == 2 and prof["dispatch"][0] == 6
+    # dispatches: x forward and dy backward per partition; with two partitions no T_DI buffer is
+    # shared, so backward finds T_DI where forward left it and does not dispatch x again
+    assert prof["gemm_dgelu"][0] == 2 and prof["gemm_dgrad"][0] == 2 and prof["dispatch"][0] == 4
     assert all(ms > 0 for cnt, ms in prof.values() if cnt)
 
 
