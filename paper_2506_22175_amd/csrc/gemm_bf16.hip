@@ -360,11 +360,9 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
             //           parts have landed too, and nobody reads stage t any more);
             //   block 1 multiplies k 16..31, reads k 0..15 of tile t+1 into the first
             //           fragment set and requests the first half of tile t+5 into stage t.
-            // Up to four tiles (128 KB) are in flight towards a CU.  (Stores of the
-            // previous epilogue may still be counted by vmcnt; they are older than the
-            // loads waited for, so the counts below only become stricter.)
+            // Up to four tiles (128 KB) are in flight towards a CU.
             static_assert(LPW == 8 && AT::NI == 4 && BT::NI == 4, "load schedule below assumes 4 + 4 loads per wave per tile");
-            if (first) wait_vmcnt<3 * LPW + LPW / 2>();            // tile 0 is in (later tiles: waited for in the epilogue)
+            if (first) wait_vmcnt<3 * LPW + LPW / 2>();            // tile 0 is in (later tiles: waited for at the handover)
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             bf16x8 F0[8], F1[8];
@@ -411,7 +409,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
             // end reads as zeros.
             int st_cur = SB, st_free = SB ^ 1;
             for (int kt = 0; kt < KT; ++kt) {
-                if (kt > 0 || first) wait_vmcnt<0>();                // (a later tile's tile 0: waited for in the epilogue)
+                if (kt > 0 || first) wait_vmcnt<0>();                // (a later tile's tile 0: waited for at the handover)
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
                 char* cs = smem + st_cur * STAGE;
@@ -563,12 +561,11 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
             if (i == 0 && vn >= 0) issue_early(ta2, tb2);
         }
         if (vn < 0) break;
-        // Tile 0 of the next tile has landed: its loads were issued after the first pass, every
-        // later pass issued at least NPIECE stores per wave, and memory operations retire in
-        // order, so whatever may still be counted is younger.
-        constexpr int ALLOW = C::PIPE ? 2 * LPW : LPW;
-        static_assert((TM - 1) * NPIECE >= ALLOW, "not enough younger stores to hide behind");
-        wait_vmcnt<ALLOW>();
+        // Everything this wave has in flight is through: the next tile's first operand tiles have
+        // landed and the epilogue's stores are written.  (Counting on the stores being younger than
+        // the loads would save waiting for the last of them, but the main loop's third wait would
+        // wait for them anyway: vmcnt retires in order.)
+        wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();                // every wave is done with the staging stages
         asm volatile("" ::: "memory");
         issue_late(ta2, tb2);
