@@ -310,7 +310,7 @@ def main():
     ap.add_argument("--reuse", type=int, default=2, help="0 keep all, 1 share buffers, 2 share + recompute")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--single-stream", action="store_true")
-    ap.add_argument("--cpu-tokens", type=int, default=2048)
+    ap.add_argument("--cpu-tokens", type=int, default=16384, help="tokens of the workload the CPU oracle is timed on")
     ap.add_argument("--graph", action="store_true", help="replay a captured HIP graph of the step (no per-kernel timing)")
     ap.add_argument("--accumulate", action="store_true",
                     help="weight gradients are added to the buffers (default: each step overwrites them)")
