@@ -75,7 +75,7 @@ struct TileCfg {
     static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
     static constexpr int LDS_BYTES = NS * STAGE_BYTES;
     // one wave per SIMD: the main loop is written out instruction by instruction
-    static constexpr bool PIPE = (WAVES == 4 && OCC == 1 && BK == 32 && NS == 5 && TM == 4 && TN == 4);
+    static constexpr bool PIPE = (BK == 32 && NS == 5);
     static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds the CU's 160 KB");
     static_assert(BK == 32 || BK == 64, "tile depth");
 };
@@ -222,8 +222,14 @@ __device__ __forceinline__ void wait_vmcnt() {
 // such statements, the LDS reads and the loads into LDS in the order they are written,
 // which is what the hand-scheduled loop below relies on (it still allocates registers
 // and inserts the s_waitcnt lgkmcnt for LDS reads it issued itself).
+template <bool ACC_IN_AGPR>
 __device__ __forceinline__ void mfma_pinned(floatx16& acc, const bf16x8& a, const bf16x8& b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b) : "memory");
+    // accumulators live in the AGPR half of the register file when a wave owns 512 registers,
+    // in ordinary VGPRs when two waves share a SIMD
+    if constexpr (ACC_IN_AGPR)
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b) : "memory");
+    else
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b) : "memory");
 }
 
 struct TileCoord { int e, tn, m0, n0, Mdim, Kdim, KT; };
@@ -350,9 +356,10 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
         if constexpr (C::PIPE) {
-            // One wave per SIMD, so nothing hides a stall: every LDS read and every load into
-            // LDS sits between two matrix instructions, one per instruction, and the data a
-            // block of 16 matrix instructions needs was requested during the block before.
+            // Hand-scheduled loop (with one wave per SIMD nothing else hides a stall): every
+            // LDS read and every load into LDS sits between two matrix instructions, one per
+            // instruction, and the data a block of TM x TN matrix instructions needs was
+            // requested during the block before.
             // A tile is 32 k = two such blocks; the ring holds five tiles.  In iteration t
             //   block 0 multiplies k 0..15 of tile t, reads k 16..31 of it into the second
             //           fragment set and requests the second half of tile t+4;
@@ -361,16 +368,16 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
             //   block 1 multiplies k 16..31, reads k 0..15 of tile t+1 into the first
             //           fragment set and requests the first half of tile t+5 into stage t.
             // Up to four tiles (128 KB) are in flight towards a CU.
-            static_assert(LPW == 8 && AT::NI == 4 && BT::NI == 4, "load schedule below assumes 4 + 4 loads per wave per tile");
+            constexpr int MB = TM * TNN;                 // matrix instructions per block
+            constexpr int FR = TM + TNN;                 // fragments per block: A rows first, then B columns
+            static_assert(LPW % 2 == 0 && FR + LPW / 2 <= MB, "one LDS read or load per matrix instruction");
             if (first) wait_vmcnt<3 * LPW + LPW / 2>();            // tile 0 is in (later tiles: waited for at the handover)
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            bf16x8 F0[8], F1[8];
+            bf16x8 F0[FR], F1[FR];
 #pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                F0[f] = fa[f].read(smem + SB * STAGE, 0);
-                F0[4 + f] = fb[f].read(smem + SB * STAGE + A_BYTES, 0);
-            }
+            for (int f = 0; f < FR; ++f)
+                F0[f] = f < TM ? fa[f].read(smem + SB * STAGE, 0) : fb[f - TM].read(smem + SB * STAGE + A_BYTES, 0);
             int st = SB;
 #pragma unroll 1
             for (int kt = 0; kt < KT; ++kt) {
@@ -380,22 +387,22 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                 char* nxt = smem + stn * STAGE;
                 char* prv = smem + stp * STAGE;
 #pragma unroll
-                for (int m = 0; m < 16; ++m) {
-                    mfma_pinned(acc[m >> 2][m & 3], F0[4 + (m & 3)], F0[m >> 2]);
-                    if (m < 4) F1[m] = fa[m].read(cs, 1);
-                    else if (m < 8) F1[m] = fb[m - 4].read(cs + A_BYTES, 1);
-                    else if (m < 12) request(ta, tb, prv, (kt + 4) * BK, LPW / 2 + m - 8);
+                for (int m = 0; m < MB; ++m) {
+                    mfma_pinned<C::OCC == 1>(acc[m / TNN][m % TNN], F0[TM + m % TNN], F0[m / TNN]);
+                    if (m < TM) F1[m] = fa[m].read(cs, 1);
+                    else if (m < FR) F1[m] = fb[m - TM].read(cs + A_BYTES, 1);
+                    else if (m < FR + LPW / 2) request(ta, tb, prv, (kt + 4) * BK, LPW / 2 + m - FR);
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave no longer reads stage t
                 wait_vmcnt<3 * LPW>();                               // its part of tile t+1 is in
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
 #pragma unroll
-                for (int m = 0; m < 16; ++m) {
-                    mfma_pinned(acc[m >> 2][m & 3], F1[4 + (m & 3)], F1[m >> 2]);
-                    if (m < 4) F0[m] = fa[m].read(nxt, 0);
-                    else if (m < 8) F0[m] = fb[m - 4].read(nxt + A_BYTES, 0);
-                    else if (m < 12) request(ta, tb, cs, (kt + 5) * BK, m - 8);
+                for (int m = 0; m < MB; ++m) {
+                    mfma_pinned<C::OCC == 1>(acc[m / TNN][m % TNN], F1[TM + m % TNN], F1[m / TNN]);
+                    if (m < TM) F0[m] = fa[m].read(nxt, 0);
+                    else if (m < FR) F0[m] = fb[m - TM].read(nxt + A_BYTES, 0);
+                    else if (m < FR + LPW / 2) request(ta, tb, cs, (kt + 5) * BK, m - FR);
                 }
                 st = stn;
             }
@@ -577,30 +584,38 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     }
 }
 
-// Tile shapes in use.  Both cover 256 x 256 per workgroup (the L2-to-CU traffic per
-// flop that the chip can sustain asks for no less).  The four-wave shape reads a third
-// less from LDS and has the hand-scheduled loop; it wins where the loop dominates
-// (K = H, and the weight-gradient GEMMs).  The eight-wave shape keeps two waves per
-// SIMD, which hides the latencies of the arithmetic-heavy GeLU epilogues better; it
-// wins for the K = M GEMMs that carry them.  MOE_GEMM_CFG overrides the choice at
-// build time for experiments (3: eight waves everywhere, 6: four waves everywhere).
-typedef TileCfg<256, 256, 64, 2, 2, 4, 2> Cfg8;    // 8 waves of 128x64, ring of 2 x 64 k
-typedef TileCfg<256, 256, 32, 5, 2, 2, 1> Cfg4;    // 4 waves of 128x128, ring of 5 x 32 k, hand-scheduled loop
+// Tile shapes in use.  All cover 256 x 256 per workgroup (the L2-to-CU traffic per flop
+// that the chip can sustain asks for no less).
+//   Cfg4   four waves of 128x128, one per SIMD: reads a third less from LDS than the
+//          eight-wave shapes; wins where the loop dominates (plain stores, weight gradients).
+//   Cfg8P  eight waves of 128x64, two per SIMD, same ring and hand-scheduled loop: the second
+//          wave hides the latencies of the arithmetic-heavy GeLU epilogue (the four-wave
+//          shape is slower there), and the loop is 5 % faster than the compiler-scheduled one.
+//   Cfg8   eight waves, ring of 2 x 64 k, compiler-scheduled loop: for the GeLU-backward
+//          GEMM, whose two operands are both K-contiguous - 64 k per tile fetches whole
+//          128-byte lines of them, 32 k would fetch half lines, which costs what the better
+//          loop gains.
+// MOE_GEMM_CFG overrides the choice at build time for experiments (3: Cfg8 everywhere,
+// 6: Cfg4 everywhere, 7: Cfg8P for both GeLU epilogues).
+typedef TileCfg<256, 256, 64, 2, 2, 4, 2> Cfg8;
+typedef TileCfg<256, 256, 32, 5, 2, 2, 1> Cfg4;
+typedef TileCfg<256, 256, 32, 5, 2, 4, 2> Cfg8P;
 #ifndef MOE_GEMM_CFG
 #define MOE_GEMM_CFG 0
 #endif
 template <int EPI> struct CfgFor {
 #if MOE_GEMM_CFG == 3
     typedef Cfg8 type;
-#elif MOE_GEMM_CFG == 6
-    typedef Cfg4 type;
 #else
     typedef Cfg4 type;
 #endif
 };
 #if MOE_GEMM_CFG == 0
-template <> struct CfgFor<EPI_GELU> { typedef Cfg8 type; };
+template <> struct CfgFor<EPI_GELU> { typedef Cfg8P type; };
 template <> struct CfgFor<EPI_DGELU> { typedef Cfg8 type; };
+#elif MOE_GEMM_CFG == 7
+template <> struct CfgFor<EPI_GELU> { typedef Cfg8P type; };
+template <> struct CfgFor<EPI_DGELU> { typedef Cfg8P type; };
 #endif
 typedef CfgFor<EPI_DGELU>::type CfgDgelu;
 
