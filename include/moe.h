@@ -29,6 +29,11 @@
  *     partition, R_p = E*C_p rows of one partition's expert-contiguous buffers.
  *   - rows of a partition buffer at or beyond counts[p][e] inside expert e's
  *     C_p-row segment are padding: never read as data, contents unspecified.
+ *   - host-side state (a pool of events, the launch counters, the timing
+ *     records) is process-wide and unsynchronised: call the library from one
+ *     host thread at a time.  Calls on different streams may overlap on the GPU;
+ *     the bf16 GEMMs launch one persistent workgroup per CU, so two GEMMs that
+ *     overlap share the CUs by whole workgroups.
  */
 #ifndef MOE_H
 #define MOE_H

@@ -192,6 +192,40 @@ def test_offloading_needs_its_own_entry_point_and_pinned_memory(runner):
     assert np.isfinite(runner.to_host(st.y)).all()
 
 
+def _random_case(i):
+    rng = np.random.default_rng(1000 + i)
+    dt = "bf16" if i % 2 == 0 else "f32"
+    n = int(rng.choice([1, 2, 3, 4]))
+    T = n * int(rng.integers(8, 160))
+    M = 8 * int(rng.integers(1, 41))
+    H = 8 * int(rng.integers(1, 51))
+    E = int(rng.integers(1, 21))
+    k = int(rng.integers(1, min(4, E) + 1))
+    cf = float(rng.choice([0.3, 0.75, 1.0, 1.25, 2.5]))
+    mode = int(rng.integers(0, 6))
+    renorm = int(rng.integers(0, 2))
+    return dict(T=T, M=M, H=H, E=E, k=k, cf=cf, dt=dt, n=n, mode=mode, renorm=renorm)
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_random_configurations_full_parity(oracle, runner, i):
+    """Seeded random shapes, partition counts, memory modes (offloading included) and gate variants."""
+    c = _random_case(i)
+    s = synth.custom_shape(c["T"], c["M"], c["H"], c["E"], c["k"], c["cf"], dtype=c["dt"], x_std=1.0, w_std=0.05,
+                           name=f"random{i}")
+    d = synth.make_inputs(s, seed=i)
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], s.k, s.capacity_factor, c["n"],
+                          gate_bias=d.get("gate_bias"), renormalize=bool(c["renorm"]))
+    g = runner.run_layer_step(s, d, c["n"], c["mode"], gate_renormalize=c["renorm"])
+    _check_routing(g, r)
+    names = ["y", "dx", "dW1", "dW2"]
+    if np.abs(r["dWg"]).max() > 1e-12:        # one choice renormalised, or one expert: the gate gets no gradient
+        names.append("dWg")
+    else:
+        assert np.abs(g["dWg"]).max() <= 1e-6 * max(np.abs(g["dW1"]).max(), 1e-30)
+    _check_values(g, r, TOL[c["dt"]], names=tuple(names))
+
+
 def test_results_do_not_depend_on_streams_or_reuse_mode(runner):
     """Same kernels, same order of accumulation: one stream or two, and the three
     memory modes, give identical routing and values that agree to rounding."""
