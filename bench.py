@@ -143,7 +143,9 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
 
     # HBM-bound permutations: algorithmic bytes = rows read + rows written
     n_disp_per_step = 1 + (2 if (reuse in (1, 2, 4) and n > 2) else 1)   # x forward; dy (+ x again when T_DI buffers are shared) backward
-    bytes_dispatch = 2.0 * R * M * es                       # per dispatch of all partitions
+    # dispatch reads every token row once, however many experts it goes to, and writes the kept rows
+    # (counting a read per kept row, 2*R rows, would flatter the kernel by a quarter at k = 2)
+    bytes_dispatch = (R + T) * M * es + T * k * 4.0         # per dispatch of all partitions
     bytes_combine = (R + T) * M * es + T * k * 8.0
     bytes_dbwd = (R + T) * M * es + T * shape.E * 4.0
     hbm = {}

@@ -12,6 +12,23 @@ namespace moe {
 constexpr int PERM_THREADS = 256;
 constexpr int PERM_WAVES = PERM_THREADS / 64;
 
+// 16-byte row accesses; NT = non-temporal (the row is read or written once per kernel)
+typedef unsigned u32x4_hw __attribute__((ext_vector_type(4)));
+template <bool NT> __device__ __forceinline__ uint4 ld_row(const uint4* p) {
+    if (NT) {
+        u32x4_hw v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_hw*>(p));
+        return make_uint4(v[0], v[1], v[2], v[3]);
+    }
+    return *p;
+}
+template <bool NT> __device__ __forceinline__ void st_row(uint4* p, const uint4& u) {
+    if (NT) {
+        u32x4_hw v = {u.x, u.y, u.z, u.w};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4_hw*>(p));
+    } else {
+        *p = u;
+    }
+}
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -40,7 +57,7 @@ __global__ __launch_bounds__(PERM_THREADS) void dispatch_kernel(
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             int c = c0 + u * 64 + lane;
-            if (c < U) v[u] = in[c];
+            if (c < U) v[u] = ld_row<true>(in + c);
         }
         for (int j = 0; j < k; ++j) {
             if (s[j] < 0) continue;
@@ -49,7 +66,7 @@ __global__ __launch_bounds__(PERM_THREADS) void dispatch_kernel(
             for (int u = 0; u < 4; ++u) {
                 int c = c0 + u * 64 + lane;
                 if (c < U) {
-                    out[c] = v[u];
+                    st_row<false>(out + c, v[u]);
                     if (WITH_DW) {
                         uint4 o = reinterpret_cast<const uint4*>(saved + (size_t)s[j] * M)[c];
                         const T* a = reinterpret_cast<const T*>(&v[u]);
@@ -124,7 +141,7 @@ __global__ __launch_bounds__(PERM_THREADS) void combine_kernel(
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int c = c0 + u * 64 + lane;
-                v[u] = c < U ? in[c] : make_uint4(0, 0, 0, 0);
+                v[u] = c < U ? ld_row<true>(in + c) : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -137,7 +154,7 @@ __global__ __launch_bounds__(PERM_THREADS) void combine_kernel(
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int c = c0 + u * 64 + lane;
-            if (c < U) out[c] = Unit<T>::from_float(acc[u]);
+            if (c < U) st_row<false>(out + c, Unit<T>::from_float(acc[u]));
         }
     }
 }
@@ -232,6 +249,152 @@ __global__ __launch_bounds__(DXF_THREADS) void dispatch_bwd_f32lds_kernel(
                     if (c < U) out[c] = Unit<T>::from_float(acc[a][u]);
                 }
             }
+        }
+    }
+}
+
+// dx[t] = sum_j dDI[slot[t,j]] + dL[t,:] Wg^T for bfloat16 storage, with the gate term on the
+// matrix cores.  A lane owns eight consecutive columns (a wavefront 512, so every row access is
+// a coalesced 1 KB), and its gate weights are the second operand of
+// v_mfma_f32_4x4x4_16B_bf16: that instruction multiplies sixteen independent 4x4 blocks, block
+// b = lane/4, D_b[i][j] += sum_k A_b[i][k] B_b[k][j], lane 4b+j holding column j of B_b and of
+// D_b (rows i in its four result registers) and lane 4b+i holding row i of A_b.  With
+// A_b[i][k] = dL[token i][expert 4g+k] (the same four tokens in every block) and
+// B_b[k][j] = Wg[column of lane 4b+j][expert 4g+k], one instruction per column and expert
+// group gives a lane the gate term of four tokens at one of its columns, at 1/8 of the issue
+// slots of float FMAs.  dL is split into two bfloat16 terms (hi + lo), which keeps 16 bits of
+// its mantissa; Wg is bfloat16 already.  The kernel is bound by the latency of its row reads,
+// so it is built for many wavefronts: the gate weights stay in LDS (read again every round)
+// rather than in 64 registers, which lets four wavefronts per SIMD run.
+typedef short bf16x4_hw __attribute__((ext_vector_type(4)));
+typedef float f32x4_hw __attribute__((ext_vector_type(4)));
+constexpr int DXM_TOK = 16;          // tokens per token group
+constexpr int DXM_TG = 2;            // token groups per workgroup (they share the gate weights in LDS)
+template <int EG>                    // expert groups of four: E <= 4*EG
+__global__ __launch_bounds__(PERM_THREADS * DXM_TG, 2) void dispatch_bwd_mfma_kernel(
+    const bf16_t* __restrict__ dDI, const int* __restrict__ slot, const float* __restrict__ dL,
+    const bf16_t* __restrict__ Wg, bf16_t* __restrict__ dx, int t_begin, int t_count, int M, int E, int k) {
+    const int ct = threadIdx.x % PERM_THREADS;                       // column thread
+    const int tg = __builtin_amdgcn_readfirstlane(threadIdx.x / PERM_THREADS);
+    const int c = (blockIdx.x * PERM_THREADS + ct) * 8;
+    const bool c_ok = c < M;                       // lanes beyond the row still feed the A operand
+    const int lane = threadIdx.x & 63;
+    const int tl0 = min((blockIdx.y * DXM_TG + tg) * DXM_TOK, t_count);
+    const int tl1 = min(tl0 + DXM_TOK, t_count);
+    // rows of four tokens, choices j0 and j0 + 1: eight 16-byte reads in flight per lane
+    auto request = [&](int tb, int j0, uint4 (&raw)[4][2]) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const int sj = (tb + u < tl1 && j0 + jj < k) ? slot[(size_t)(t_begin + tb + u) * k + j0 + jj] : -1;
+                raw[u][jj] = make_uint4(0, 0, 0, 0);
+                if (c_ok && sj >= 0) raw[u][jj] = ld_row<true>(reinterpret_cast<const uint4*>(dDI + (size_t)sj * M + c));
+            }
+    };
+    // gate gradients of this lane's token (tb + lane%4) for the A operand
+    auto request_dl = [&](int tb, float4 (&dl)[EG]) {
+        const int ta = tb + (lane & 3);
+#pragma unroll
+        for (int g = 0; g < EG; ++g) {
+            dl[g] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (ta < tl1) {
+                const float* row = dL + (size_t)(t_begin + ta) * E + 4 * g;
+                if (E == 4 * EG) {
+                    dl[g] = *reinterpret_cast<const float4*>(row);
+                } else {
+                    if (4 * g + 0 < E) dl[g].x = row[0];
+                    if (4 * g + 1 < E) dl[g].y = row[1];
+                    if (4 * g + 2 < E) dl[g].z = row[2];
+                    if (4 * g + 3 < E) dl[g].w = row[3];
+                }
+            }
+        }
+    };
+    uint4 raw[4][2];
+    float4 dl[EG];
+    request_dl(tl0, dl);                           // the first round's rows travel during the prologue
+    request(tl0, 0, raw);
+
+    // Gate weights of this workgroup's columns into LDS with coalesced 16-byte reads.  A lane's
+    // piece (64*EG bytes: 8 columns x 4*EG experts) is padded by 16 bytes so that the reads of a
+    // wavefront spread over all banks.
+    extern __shared__ __attribute__((aligned(16))) char dxm_smem[];
+    constexpr int CHUNK = 64 * EG;
+    constexpr int PITCH = CHUNK + 16;
+    {
+        const int c_base = blockIdx.x * PERM_THREADS * 8;
+        const int ncols = min(PERM_THREADS * 8, M - c_base);
+        if (E == 4 * EG) {
+            const uint4* src = reinterpret_cast<const uint4*>(Wg + (size_t)c_base * E);
+            const int pieces = ncols * EG / 2;                        // 16-byte pieces of the slice
+            for (int q = threadIdx.x; q < pieces; q += PERM_THREADS * DXM_TG) {
+                const int byte = q * 16;
+                *reinterpret_cast<uint4*>(dxm_smem + (byte / CHUNK) * PITCH + byte % CHUNK) = src[q];
+            }
+        } else {
+            for (int q = threadIdx.x; q < ncols * 4 * EG; q += PERM_THREADS * DXM_TG) {
+                const int col = q / (4 * EG), e = q % (4 * EG);
+                const bf16_t v = e < E ? Wg[(size_t)(c_base + col) * E + e] : (bf16_t)0;
+                *reinterpret_cast<bf16_t*>(dxm_smem + (col / 8) * PITCH + (col % 8) * 8 * EG + e * 2) = v;
+            }
+        }
+    }
+    __syncthreads();
+    for (int tb = tl0; tb < tl1; tb += 4) {
+        if (tb > tl0) {
+            request_dl(tb, dl);
+            request(tb, 0, raw);
+        }
+        bf16x4_hw a_hi[EG], a_lo[EG];
+#pragma unroll
+        for (int g = 0; g < EG; ++g) {
+            const float v[4] = {dl[g].x, dl[g].y, dl[g].z, dl[g].w};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bf16_t h = f32_to_bf16(v[r]);
+                a_hi[g][r] = (short)h;
+                a_lo[g][r] = (short)f32_to_bf16(v[r] - bf16_to_f32(h));
+            }
+        }
+        f32x4_hw gate[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) gate[i] = f32x4_hw{0.0f, 0.0f, 0.0f, 0.0f};
+        int my_off = ct * PITCH;                   // opaque: the compiler must not keep the weights in registers
+        asm volatile("" : "+v"(my_off));
+#pragma unroll
+        for (int g = 0; g < EG; ++g)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const bf16x4_hw w = *reinterpret_cast<const bf16x4_hw*>(dxm_smem + my_off + (i * EG + g) * 8);
+                gate[i] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_hi[g], w, gate[i], 0, 0, 0);
+                gate[i] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_lo[g], w, gate[i], 0, 0, 0);
+            }
+        float acc[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float r0[8], r1[8];
+            Unit<bf16_t>::to_float(raw[u][0], r0);
+            Unit<bf16_t>::to_float(raw[u][1], r1);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[u][i] = gate[i][u] + (r0[i] + r1[i]);
+        }
+        for (int j0 = 2; j0 < k; j0 += 2) {            // further choices (k > 2)
+            request(tb, j0, raw);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float r0[8], r1[8];
+                Unit<bf16_t>::to_float(raw[u][0], r0);
+                Unit<bf16_t>::to_float(raw[u][1], r1);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[u][i] += r0[i] + r1[i];
+            }
+        }
+        if (c_ok) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (tb + u < tl1)
+                    st_row<false>(reinterpret_cast<uint4*>(dx + (size_t)(t_begin + tb + u) * M + c), Unit<bf16_t>::from_float(acc[u]));
         }
     }
 }
@@ -499,6 +662,23 @@ static moe_status dispatch_t(const Dims& d, int part, const void* src, const int
 template <typename T>
 static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const int* slot, const float* dL,
                                  const void* Wg, void* dx, hipStream_t s) {
+    if (sizeof(T) == 2 && d.E <= 16) {      // more experts: the gate weights no longer fit a lane's registers
+        dim3 grid((d.M / 8 + PERM_THREADS - 1) / PERM_THREADS, (d.Tp + DXM_TOK * DXM_TG - 1) / (DXM_TOK * DXM_TG));
+#define LAUNCH_DXM(EG) do { \
+        const int lds = PERM_THREADS * (64 * EG + 16); \
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(dispatch_bwd_mfma_kernel<EG>), \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds)); \
+        hipLaunchKernelGGL((dispatch_bwd_mfma_kernel<EG>), grid, dim3(PERM_THREADS * DXM_TG), lds, s, \
+        (const bf16_t*)dDI, slot, dL, (const bf16_t*)Wg, (bf16_t*)dx, part * d.Tp, d.Tp, d.M, d.E, d.k); } while (0)
+        ProfScope ps(PK_DISPATCH_BWD, s);
+        if (d.E <= 4) LAUNCH_DXM(1);
+        else if (d.E <= 8) LAUNCH_DXM(2);
+        else LAUNCH_DXM(4);
+#undef LAUNCH_DXM
+        count_launch(LC_PERMUTE);
+        MOE_CHECK_LAUNCH();
+        return MOE_OK;
+    }
     const size_t wg_float_bytes = (size_t)d.M * d.E * sizeof(float);
     if (wg_float_bytes <= 128 * 1024) {
         auto kern = dispatch_bwd_f32lds_kernel<T>;
