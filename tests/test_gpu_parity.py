@@ -101,6 +101,10 @@ CASES = [
     # gate matrix too large for LDS: streamed in pieces by the gate, register-held in dispatch backward
     ("big_gate_bf16", 256, 2560, 64, 32, 2, 1.0, "bf16", 2, None),
     ("big_gate_f32", 128, 1088, 32, 33, 3, 1.0, "f32", 1, None),
+    # rows wider than the 2048 columns one workgroup of the dispatch-backward kernel covers, four
+    # choices per token, a last round of two tokens; then an expert count that is no multiple of four
+    ("wide_rows_k4_bf16", 102, 2304, 64, 16, 4, 1.0, "bf16", 1, None),
+    ("wide_rows_odd_experts_bf16", 90, 2056, 40, 7, 3, 1.5, "bf16", 3, None),
 ]
 
 
