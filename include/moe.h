@@ -174,7 +174,10 @@ moe_status moe_gate_bwd(const moe_config* cfg, int32_t part, const void* x, cons
 moe_status moe_gate_scratch_bytes(const moe_config* cfg, size_t* bytes);
 
 /* Dispatch backward S' of partition `part`:
- * dx[t] = sum over kept j of dDI[slot[t,j]] + dL[t,:] Wg^T.   dx [T,M] out. */
+ * dx[t] = sum over kept j of dDI[slot[t,j]] + dL[t,:] Wg^T.   dx [T,M] out.
+ * Float accumulation; for bfloat16 storage and E <= 16 the gate term runs on the
+ * matrix cores with dL carried as the sum of two bfloat16 numbers (16 bits of its
+ * mantissa), otherwise as float multiply-adds. */
 moe_status moe_dispatch_bwd(const moe_config* cfg, int32_t part, const void* dDI, const int32_t* slot,
                             const float* dL, const void* Wg, void* dx, void* stream);
 
