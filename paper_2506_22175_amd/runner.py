@@ -154,14 +154,19 @@ class LayerState:
 
 
 def run_layer_step(shape, inp: Dict[str, np.ndarray], n_partitions=1, reuse=0, poison=True,
-                   second_stream=True, device="cuda:0", gate_renormalize=0) -> Dict[str, np.ndarray]:
-    """One step of the HIP path on a synth.MoEShape-like object; returns host arrays."""
+                   second_stream=True, device="cuda:0", gate_renormalize=0, grad_overwrite=0) -> Dict[str, np.ndarray]:
+    """One step of the HIP path on a synth.MoEShape-like object; returns host arrays.  With
+    grad_overwrite the weight-gradient buffers start as NaN instead of zero: the step must store them."""
     st = LayerState(shape.T, shape.M, shape.H, shape.E, shape.k, shape.capacity_factor, n_partitions,
-                    shape.dtype, reuse, device, second_stream, gate_renormalize=gate_renormalize)
+                    shape.dtype, reuse, device, second_stream, grad_overwrite=grad_overwrite,
+                    gate_renormalize=gate_renormalize)
     st.upload(inp)
     if poison:
         st.poison()
     st.zero_grads()
+    if grad_overwrite:
+        for t in (st.dWg, st.dW1, st.dW2):
+            t.fill_(float("nan"))
     st.step()
     out = st.results()
     out["C_p"] = st.C_p
