@@ -666,8 +666,12 @@ static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const
         dim3 grid((d.M / 8 + PERM_THREADS - 1) / PERM_THREADS, (d.Tp + DXM_TOK * DXM_TG - 1) / (DXM_TOK * DXM_TG));
 #define LAUNCH_DXM(EG) do { \
         const int lds = PERM_THREADS * (64 * EG + 16); \
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(dispatch_bwd_mfma_kernel<EG>), \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds)); \
+        static bool attr_done = false; \
+        if (!attr_done) { \
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(dispatch_bwd_mfma_kernel<EG>), \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds)); \
+            attr_done = true; \
+        } \
         hipLaunchKernelGGL((dispatch_bwd_mfma_kernel<EG>), grid, dim3(PERM_THREADS * DXM_TG), lds, s, \
         (const bf16_t*)dDI, slot, dL, (const bf16_t*)Wg, (bf16_t*)dx, part * d.Tp, d.Tp, d.M, d.E, d.k); } while (0)
         ProfScope ps(PK_DISPATCH_BWD, s);
@@ -682,8 +686,12 @@ static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const
     const size_t wg_float_bytes = (size_t)d.M * d.E * sizeof(float);
     if (wg_float_bytes <= 128 * 1024) {
         auto kern = dispatch_bwd_f32lds_kernel<T>;
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)wg_float_bytes));
+        static size_t attr_bytes = 0;                 // largest size asked for so far
+        if (wg_float_bytes > attr_bytes) {
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)wg_float_bytes));
+            attr_bytes = wg_float_bytes;
+        }
         int blocks = (d.Tp + 2 * DXF_WAVES - 1) / (2 * DXF_WAVES);
         const int cap = wg_float_bytes > 64 * 1024 ? 256 : 512;      // workgroups that fit the chip at once
         if (blocks > cap) blocks = cap;

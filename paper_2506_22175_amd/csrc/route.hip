@@ -209,8 +209,12 @@ static moe_status launch_route(const Dims& d, const void* x, const void* Wg, con
     }
     size_t lds = ((size_t)MC * EP + (size_t)ROUTE_WAVES * TB * EP) * sizeof(float);
     auto kern = route_kernel<T, EP, TB>;
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds));
+    static size_t attr_bytes = 0;                     // largest size asked for so far (per instantiation)
+    if (lds > attr_bytes) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds));
+        attr_bytes = lds;
+    }
     int ngroups = (d.T + ROUTE_WAVES * TB - 1) / (ROUTE_WAVES * TB);
     const int cap = lds > 80 * 1024 ? 256 : 512;      // one or two workgroups per CU fit
     int grid = ngroups < cap ? ngroups : cap;
