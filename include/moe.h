@@ -83,6 +83,14 @@ typedef struct {
                                (what the paper's k = 1 gate implies); 1: they are divided
                                by their sum over the token's k choices, drops included
                                (a softmax over the chosen logits only) */
+    int32_t fuse_gather;    /* 0: forward dispatches T_I into T_DI and the first expert GEMM
+                               reads T_DI; 1: in forward the first expert GEMM reads its rows
+                               straight from T_I through the slot-to-token map, so forward runs
+                               no S kernel and writes no T_DI (one permutation unit per
+                               micro-batch instead of Table II's two); backward dispatches T_I
+                               into two partition-sized T_DI buffers for the weight-gradient
+                               GEMM, as the shared-buffer modes do.  Not with S1 and S3, which
+                               copy forward's T_DI to the host. */
 } moe_config;
 
 /* Host only.  C_p = ceil(capacity_factor * k * (T / n) / E), evaluated in double
@@ -172,6 +180,19 @@ moe_status moe_gate_bwd(const moe_config* cfg, int32_t part, const void* x, cons
                         const int32_t* topk_idx, const int32_t* slot, const float* dw,
                         const float* dw_part, float* dL, float* dWg, void* scratch, void* stream);
 moe_status moe_gate_scratch_bytes(const moe_config* cfg, size_t* bytes);
+
+/* Inverse of the slot map: rows[p][slot[t,j]] = t for every kept assignment of
+ * partition p (t counted over the whole batch).  Entries at or beyond
+ * counts[p][e] inside expert e's C_p-entry segment are not written.
+ *   slot [T,k] in; rows [n, E*C_p] int32 out. */
+moe_status moe_slot_rows(const moe_config* cfg, const int32_t* slot, int32_t* rows, void* stream);
+
+/* moe_expert_ffn_fwd with the first GEMM's operand gathered: row r of expert e is
+ * x[rows[part][e*C_p + r]] (Section II-B2's T_DI never exists; the result is the same
+ * as dispatching first, bit for bit).  x [T,M]; rows from moe_slot_rows. */
+moe_status moe_expert_ffn_fwd_gather(const moe_config* cfg, int32_t part, const void* x, const int32_t* rows,
+                                     const int32_t* counts, const void* W1, const void* W2,
+                                     void* Z, void* A, void* DO, void* stream);
 
 /* Dispatch backward S' of partition `part`:
  * dx[t] = sum over kept j of dDI[slot[t,j]] + dL[t,:] Wg^T.   dx [T,M] out.

@@ -22,6 +22,7 @@ MOE_REUSE_S1, MOE_REUSE_S2, MOE_REUSE_S3 = 3, 4, 5
 EXPORTS = [
     "moe_capacity", "moe_workspace_bytes", "moe_route", "moe_assign_slots", "moe_slot_scratch_bytes",
     "moe_dispatch", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_dw_parts", "moe_combine",
+    "moe_slot_rows", "moe_expert_ffn_fwd_gather",
     "moe_gate_bwd", "moe_gate_scratch_bytes", "moe_dispatch_bwd", "moe_layer_step",
     "moe_layer_forward", "moe_layer_backward", "moe_launch_counts", "moe_status_string",
     "moe_last_error", "moe_profile_enable", "moe_profile_read",
@@ -41,13 +42,14 @@ class MoEError(RuntimeError):
 class MoEConfig(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("M", ctypes.c_int32), ("H", ctypes.c_int32), ("E", ctypes.c_int32),
                 ("k", ctypes.c_int32), ("capacity_factor", ctypes.c_float), ("n_partitions", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("reuse", ctypes.c_int32), ("grad_overwrite", ctypes.c_int32), ("gate_renormalize", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("reuse", ctypes.c_int32), ("grad_overwrite", ctypes.c_int32), ("gate_renormalize", ctypes.c_int32),
+                ("fuse_gather", ctypes.c_int32)]
 
 
 def make_config(T, M, H, E, k, capacity_factor, n_partitions=1, dtype=MOE_BF16, reuse=MOE_REUSE_NONE,
-                grad_overwrite=0, gate_renormalize=0) -> MoEConfig:
+                grad_overwrite=0, gate_renormalize=0, fuse_gather=0) -> MoEConfig:
     return MoEConfig(int(T), int(M), int(H), int(E), int(k), float(capacity_factor), int(n_partitions),
-                     int(dtype), int(reuse), int(grad_overwrite), int(gate_renormalize))
+                     int(dtype), int(reuse), int(grad_overwrite), int(gate_renormalize), int(fuse_gather))
 
 
 _lib = None
@@ -168,6 +170,15 @@ def moe_assign_slots(cfg, topk_idx, topk_w, slot, counts, slot_w, scratch, strea
 def moe_dispatch(cfg, part, src, slot, DI, dO_saved=None, dw=None, stream=None):
     _check(lib().moe_dispatch(_cfg(cfg), ctypes.c_int32(part), _p(src), _p(slot), _p(DI), _p(dO_saved), _p(dw),
                               _s(stream)), "moe_dispatch")
+
+
+def moe_slot_rows(cfg, slot, rows, stream=None):
+    _check(lib().moe_slot_rows(_cfg(cfg), _p(slot), _p(rows), _s(stream)), "moe_slot_rows")
+
+
+def moe_expert_ffn_fwd_gather(cfg, part, x, rows, counts, W1, W2, Z, A, DO, stream=None):
+    _check(lib().moe_expert_ffn_fwd_gather(_cfg(cfg), ctypes.c_int32(part), _p(x), _p(rows), _p(counts), _p(W1),
+                                           _p(W2), _p(Z), _p(A), _p(DO), _s(stream)), "moe_expert_ffn_fwd_gather")
 
 
 def moe_expert_ffn_fwd(cfg, part, DI, counts, W1, W2, Z, A, DO, stream=None):

@@ -124,6 +124,7 @@ struct Dims {
     int dtype, reuse;
     int overwrite;   // weight gradients are overwritten (first partition stores) instead of accumulated
     int renorm;      // combine weights are renormalised over the token's k choices
+    int fuse;        // forward's first GEMM gathers its rows from the token-major input
     size_t es;   // element size in bytes
 };
 
@@ -177,6 +178,9 @@ struct GemmArgs {
     const void* A; const void* B; void* C;
     long long a_estride, b_estride, c_estride;   // elements between experts
     int lda, ldb, ldc;
+    const int* a_rows;    // NN / NT only, may be NULL: row r of expert e is row a_rows[e*Cp + r] of A
+                          // (A is then one matrix of a_row_limit rows for all experts; a_estride unused)
+    int a_row_limit;
     const int* counts;    // [E] valid rows of this partition
     int E, Cp;            // experts, max rows per expert
     int Mo;               // TN only: output rows
@@ -203,8 +207,9 @@ int gemm_f32_dw_parts(int H);
 
 
 // ---- one partition's expert FFN (ffn.hip) ---------------------------------------
-moe_status ffn_fwd(const Dims& d, int part, const void* DI, const int* counts, const void* W1, const void* W2,
-                   void* Z, void* A, void* DO, hipStream_t s);
+// rows != NULL: DI is the token-major input [T, M] and rows[part] maps expert rows to its rows
+moe_status ffn_fwd(const Dims& d, int part, const void* DI, const int* rows, const int* counts,
+                   const void* W1, const void* W2, void* Z, void* A, void* DO, hipStream_t s);
 moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void* Z, const void* dDO,
                    const int* counts, const float* slot_w, const void* W1, const void* W2,
                    void* dZ, void* dDI, float* dW1, float* dW2, float* dw_part, hipStream_t s);

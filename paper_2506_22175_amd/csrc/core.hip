@@ -27,6 +27,9 @@ moe_status make_dims(const moe_config* cfg, Dims* d) {
     d->dtype = cfg->dtype; d->reuse = cfg->reuse;
     d->overwrite = cfg->grad_overwrite != 0;
     d->renorm = cfg->gate_renormalize != 0;
+    if (cfg->fuse_gather != 0 && cfg->fuse_gather != 1) return MOE_ERR_UNSUPPORTED;
+    if (cfg->fuse_gather && (cfg->reuse == MOE_REUSE_S1 || cfg->reuse == MOE_REUSE_S3)) return MOE_ERR_UNSUPPORTED;
+    d->fuse = cfg->fuse_gather;
     d->es = cfg->dtype == MOE_F32 ? 4 : 2;
     return MOE_OK;
 }

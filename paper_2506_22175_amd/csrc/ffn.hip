@@ -18,12 +18,13 @@ static GemmArgs base_args(const Dims& d, const int* counts_p) {
     return a;
 }
 
-moe_status ffn_fwd(const Dims& d, int part, const void* DI, const int* counts, const void* W1, const void* W2,
-                   void* Z, void* A, void* DO, hipStream_t s) {
+moe_status ffn_fwd(const Dims& d, int part, const void* DI, const int* rows, const int* counts,
+                   const void* W1, const void* W2, void* Z, void* A, void* DO, hipStream_t s) {
     const int* cp = counts + (size_t)part * d.E;
     // T_M = T_DI W1 ; A = gelu(T_M)
     GemmArgs a = base_args(d, cp);
     a.A = DI; a.lda = d.M; a.a_estride = (long long)d.Cp * d.M;
+    if (rows) { a.a_rows = rows + (size_t)part * d.Rp; a.a_row_limit = d.T; a.a_estride = 0; }
     a.B = W1; a.ldb = d.H; a.b_estride = (long long)d.M * d.H;
     a.C = A; a.ldc = d.H; a.c_estride = (long long)d.Cp * d.H;
     a.N = d.H; a.K = d.M;
@@ -109,7 +110,17 @@ extern "C" moe_status moe_expert_ffn_fwd(const moe_config* cfg, int32_t part, co
     MOE_TRY(make_dims(cfg, &d));
     MOE_TRY(check_part(d, part));
     if (!DI || !counts || !W1 || !W2 || !A || !DO) return MOE_ERR_NULL;
-    return ffn_fwd(d, part, DI, counts, W1, W2, Z, A, DO, (hipStream_t)stream);
+    return ffn_fwd(d, part, DI, nullptr, counts, W1, W2, Z, A, DO, (hipStream_t)stream);
+}
+
+extern "C" moe_status moe_expert_ffn_fwd_gather(const moe_config* cfg, int32_t part, const void* x, const int32_t* rows,
+                                                const int32_t* counts, const void* W1, const void* W2,
+                                                void* Z, void* A, void* DO, void* stream) {
+    Dims d;
+    MOE_TRY(make_dims(cfg, &d));
+    MOE_TRY(check_part(d, part));
+    if (!x || !rows || !counts || !W1 || !W2 || !A || !DO) return MOE_ERR_NULL;
+    return ffn_fwd(d, part, x, rows, counts, W1, W2, Z, A, DO, (hipStream_t)stream);
 }
 
 extern "C" moe_status moe_expert_ffn_bwd(const moe_config* cfg, int32_t part, int32_t recompute,

@@ -115,6 +115,23 @@ struct KCTile {
             voff[j] = (unsigned)(row * ld + c * 8) * 2u;
         }
     }
+    // The same tile with its rows gathered: row r of the tile is row rows[row0 + r] of the matrix P
+    // (of n_rows rows); rows at or beyond row_limit read as zeros.  Only the lane offsets differ,
+    // so the main loop is the same.
+    __device__ __forceinline__ void init_gather(const bf16_t* P, int ld, const int* rows, int row0, int row_limit,
+                                                int n_rows, int K_, int lane, int wid) {
+        K = K_;
+        rsrc = make_rsrc(P, K_ > 0 ? (unsigned)(((size_t)(n_rows - 1) * ld + K_) * 2) : 0u);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int q = wid * NI + j;
+            const int row = q * RPI + lane / CPR;
+            const int c = (lane % CPR) ^ sw(row);
+            kc[j] = c * 8;
+            const int src = row0 + row < row_limit ? rows[row0 + row] : -1;
+            voff[j] = src >= 0 ? (unsigned)(src * ld + c * 8) * 2u : OOB_OFFSET;
+        }
+    }
     __device__ __forceinline__ void load_one(char* tile, int k0, int wid, int j) const {
         const int q = wid * NI + j;
         load_to_lds(rsrc, lds_address(tile) + q * 1024, (k0 + kc[j] < K) ? voff[j] + (unsigned)k0 * 2u : OOB_OFFSET);
@@ -307,7 +324,15 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     auto bind = [&](const TileCoord& t, AT& ta_, BT& tb_) {
         const bf16_t* A = (const bf16_t*)g.A + (size_t)t.e * g.a_estride;
         const bf16_t* B = (const bf16_t*)g.B + (size_t)t.e * g.b_estride;
-        ta_.init(A, g.lda, t.m0, t.Mdim, t.Kdim, lane, wid);
+        bool gathered = false;
+        if constexpr (LAY != GEMM_TN) {
+            if (g.a_rows) {
+                ta_.init_gather((const bf16_t*)g.A, g.lda, g.a_rows + (size_t)t.e * g.Cp, t.m0, t.Mdim, g.a_row_limit,
+                                t.Kdim, lane, wid);
+                gathered = true;
+            }
+        }
+        if (!gathered) ta_.init(A, g.lda, t.m0, t.Mdim, t.Kdim, lane, wid);
         tb_.init(B, g.ldb, t.n0, g.N, t.Kdim, lane, wid);
     };
     auto request = [&](const AT& ta_, const BT& tb_, char* st, int k0, int l) {   // load l of the tile starting at k0
@@ -678,6 +703,11 @@ moe_status gemm_bf16(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStr
     const long long ldmax = a.lda > a.ldb ? a.lda : a.ldb;
     const long long rmax = a.Cp > a.K ? a.Cp : a.K;
     if ((rmax + 8 * 64) * ldmax * 2 >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
+    if (a.a_rows) {
+        // gathered rows: only for the row operand of NN / NT, and the whole matrix must stay below 2 GiB
+        if (lay == GEMM_TN || a.a_row_limit <= 0) return MOE_ERR_UNSUPPORTED;
+        if (((long long)a.a_row_limit + 1) * a.lda * 2 >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
+    }
     if (lay == GEMM_NN) return launch_lay<GEMM_NN>(epi, a, s);
     if (lay == GEMM_NT) return launch_lay<GEMM_NT>(epi, a, s);
     return launch_lay<GEMM_TN>(epi, a, s);

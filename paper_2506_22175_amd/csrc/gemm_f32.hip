@@ -42,7 +42,12 @@ __global__ __launch_bounds__(F_THREADS) void gemm_f32_kernel(GemmArgs g, int til
             int kk, mm;
             if (LAY == GEMM_TN) { mm = idx & 63; kk = idx >> 6; } else { kk = idx & 15; mm = idx >> 4; }
             float v = 0.0f;
-            if (m0 + mm < Mdim && k0 + kk < Kdim) v = A[(size_t)(m0 + mm) * a_rs + (size_t)(k0 + kk) * a_cs];
+            if (m0 + mm < Mdim && k0 + kk < Kdim) {
+                if (LAY != GEMM_TN && g.a_rows)       // gathered rows: one matrix for all experts
+                    v = ((const float*)g.A)[(size_t)g.a_rows[(size_t)e * g.Cp + m0 + mm] * a_rs + (size_t)(k0 + kk) * a_cs];
+                else
+                    v = A[(size_t)(m0 + mm) * a_rs + (size_t)(k0 + kk) * a_cs];
+            }
             As[kk][mm] = v;
             int kb, nn;
             if (LAY == GEMM_NT) { kb = idx & 15; nn = idx >> 4; } else { nn = idx & 63; kb = idx >> 6; }
@@ -109,6 +114,7 @@ static moe_status launch_f32(GemmEpilogue epi, const GemmArgs& a, hipStream_t s)
 
 moe_status gemm_f32(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
     if (a.dw_part && a.dw_parts != gemm_f32_dw_parts(a.N)) return MOE_ERR_SHAPE;
+    if (a.a_rows && (lay == GEMM_TN || a.a_row_limit <= 0)) return MOE_ERR_UNSUPPORTED;
     if (lay == GEMM_NN) return launch_f32<GEMM_NN>(epi, a, s);
     if (lay == GEMM_NT) return launch_f32<GEMM_NT>(epi, a, s);
     return launch_f32<GEMM_TN>(epi, a, s);

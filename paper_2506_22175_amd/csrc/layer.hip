@@ -29,7 +29,7 @@ struct Workspace {
     size_t Z, HT;                     // Z: nZ buffers; HT: one temporary (forward A, backward dZ)
     int nZ;
     // routing-class data
-    size_t slot_w, dw, dw_part, dL, gate_scratch, slot_scratch;
+    size_t slot_w, dw, dw_part, dL, gate_scratch, slot_scratch, rows;
     size_t bufM, bufH, dw_part_bytes;
     size_t total, saved, temp, routing;
 };
@@ -51,7 +51,8 @@ static moe_status plan(const moe_config* cfg, const Dims& d, Workspace* w) {
     w->bufM = align_up((size_t)d.Rp * d.M * d.es);
     w->bufH = align_up((size_t)d.Rp * d.H * d.es);
     const bool reuse = d.reuse != MOE_REUSE_NONE;
-    w->nDI = (reuse && d.n > 2) ? 2 : d.n;
+    // with the gathered first GEMM forward keeps no T_DI at all; backward dispatches into two buffers
+    w->nDI = ((reuse || d.fuse) && d.n > 2) ? 2 : d.n;
     w->nDO = (reuse && d.n > 2) ? 2 : d.n;
     w->nZ = mode_recomputes(d.reuse) ? 1 : mode_offloads_z(d.reuse) ? (d.n < 2 ? d.n : 2) : d.n;
     w->dDO_aliases_DO = reuse;
@@ -78,6 +79,7 @@ static moe_status plan(const moe_config* cfg, const Dims& d, Workspace* w) {
     w->dL = take((size_t)d.T * d.E * sizeof(float));
     w->gate_scratch = take(gs);
     w->slot_scratch = take(ss);
+    w->rows = take(d.fuse ? (size_t)d.n * d.Rp * sizeof(int) : 0);
     w->routing = off - r0;
     w->total = off;
     return MOE_OK;
@@ -112,6 +114,8 @@ static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace&
     MOE_TRY(moe_route(cfg, x, Wg, gate_bias, logits, topk_idx, topk_w, s0));
     MOE_TRY(moe_assign_slots(cfg, topk_idx, topk_w, slot, counts, (float*)(ws + w.slot_w),
                              ws + w.slot_scratch, s0));
+    const int* rows = d.fuse ? (const int*)(ws + w.rows) : nullptr;
+    if (d.fuse) MOE_TRY(moe_slot_rows(cfg, slot, (int*)(ws + w.rows), s0));
     HIP_TRY(hipEventRecord(evFork, s0));
     HIP_TRY(hipStreamWaitEvent(s1, evFork, 0));
 
@@ -125,7 +129,8 @@ static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace&
             // S_p.  A shared T_DI buffer was last read by C_{p-2}; R_{p-2}, already
             // queued on this stream, waited for C_{p-2}.  Its copy to the host must be through too.
             if (off_di && p >= w.nDI) HIP_TRY(hipStreamWaitEvent(s0, evDIout[p - w.nDI], 0));
-            MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
+            // (with the gathered first GEMM there is no S kernel: C_p reads T_I through the row map)
+            if (!d.fuse) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
             HIP_TRY(hipEventRecord(evS[p], s0));
             if (off_di) {
                 HIP_TRY(hipStreamWaitEvent(off->s2, evS[p], 0));
@@ -139,7 +144,8 @@ static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace&
             // with recomputation T_M is not kept: the activated rows go to the one
             // shared H-wide buffer and the pre-activation is not written at all
             void* Aout = keepZ ? (void*)(ws + w.HT) : (void*)Zbuf(p);
-            MOE_TRY(ffn_fwd(d, p, DIbuf(p), counts, W1, W2, keepZ ? Zbuf(p) : nullptr, Aout, DObuf(p), s1));
+            MOE_TRY(ffn_fwd(d, p, d.fuse ? x : (const void*)DIbuf(p), rows, counts, W1, W2, keepZ ? Zbuf(p) : nullptr,
+                            Aout, DObuf(p), s1));
             HIP_TRY(hipEventRecord(evC[p], s1));
             if (off_z) {
                 HIP_TRY(hipStreamWaitEvent(off->s2, evC[p], 0));
@@ -201,10 +207,11 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
                 MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), nullptr, nullptr, s0));
                 // T_DI from T_I again - unless every partition still has its own buffer (n <= 2 shares
                 // nothing), which then holds what forward put there
-                if (!off_di && w.nDI < n) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
+                if (!off_di && (w.nDI < n || d.fuse)) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
             } else {
                 // T_DO was kept: the combine-weight gradient is <dy_t, T_DO row>
                 MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), DObuf(p), dw, s0));
+                if (d.fuse) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
             }
             HIP_TRY(hipEventRecord(evS[p], s0));
             if (off_di || off_z) {

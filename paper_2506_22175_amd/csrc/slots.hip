@@ -69,7 +69,29 @@ __global__ __launch_bounds__(SLOT_BLOCK) void slot_assign_kernel(
     }
 }
 
+// rows[p][slot[t,j]] = t for kept assignments: the map a gathering GEMM reads its rows through
+__global__ __launch_bounds__(256) void slot_rows_kernel(const int* __restrict__ slot, int* __restrict__ rows,
+                                                        int T, int Tp, int k, int Rp) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= T * k) return;
+    const int t = i / k;
+    const int s = slot[i];
+    if (s >= 0) rows[(size_t)(t / Tp) * Rp + s] = t;
+}
+
 }  // namespace moe
+
+extern "C" moe_status moe_slot_rows(const moe_config* cfg, const int32_t* slot, int32_t* rows, void* stream) {
+    moe::Dims d;
+    MOE_TRY(moe::make_dims(cfg, &d));
+    if (!slot || !rows) return MOE_ERR_NULL;
+    const int total = d.T * d.k;
+    hipLaunchKernelGGL(moe::slot_rows_kernel, dim3((total + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                       slot, rows, d.T, d.Tp, d.k, d.Rp);
+    moe::count_launch(moe::LC_OTHER);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
 
 extern "C" moe_status moe_slot_scratch_bytes(const moe_config* cfg, size_t* bytes) {
     moe::Dims d;

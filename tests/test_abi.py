@@ -45,6 +45,10 @@ def test_argument_errors_are_status_codes():
         (B.make_config(256, 64, 128, 65, 1, 1.0), 3),          # E > 64
         (B.make_config(256, 60, 128, 4, 1, 1.0), 3),           # M % 8
         (B.make_config(256, 64, 128, 4, 1, 1.0, 1, 7), 3),     # dtype
+        (B.make_config(256, 64, 128, 4, 1, 1.0, fuse_gather=2), 3),
+        # the strategies that copy forward's T_DI to the host need a T_DI in forward
+        (B.make_config(256, 64, 128, 4, 1, 1.0, 2, B.MOE_BF16, B.MOE_REUSE_S1, fuse_gather=1), 3),
+        (B.make_config(256, 64, 128, 4, 1, 1.0, 2, B.MOE_BF16, B.MOE_REUSE_S3, fuse_gather=1), 3),
     ]
     for cfg, code in bad:
         with pytest.raises(B.MoEError) as ei:
@@ -79,3 +83,10 @@ def test_workspace_follows_the_memory_model(oracle):
             delta = oracle.paper_memory_model(R_p * n, M, H, E, n)["delta"]
             assert sizes[0] - sizes[2] == 2 * delta
         assert sizes[2] <= sizes[1] <= sizes[0] or n == 1
+        # the gathered first GEMM: forward keeps no T_DI, backward dispatches into min(n, 2) buffers;
+        # the shared-buffer modes had that many already, so only "keep everything" shrinks
+        bufM = 2 * R_p * M
+        for mode in (0, 1, 2):
+            cfg = B.make_config(T, M, H, E, k, cf, n, B.MOE_BF16, mode, fuse_gather=1)
+            saved_f = B.moe_workspace_bytes(cfg)[1]
+            assert saved_f == sizes[mode] - (bufM * (n - 2) if (mode == 0 and n > 2) else 0)

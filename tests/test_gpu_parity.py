@@ -208,7 +208,8 @@ def _random_case(i):
     cf = float(rng.choice([0.3, 0.75, 1.0, 1.25, 2.5]))
     mode = int(rng.integers(0, 6))
     renorm = int(rng.integers(0, 2))
-    return dict(T=T, M=M, H=H, E=E, k=k, cf=cf, dt=dt, n=n, mode=mode, renorm=renorm)
+    fuse = int(rng.integers(0, 2)) if mode not in (3, 5) else 0
+    return dict(T=T, M=M, H=H, E=E, k=k, cf=cf, dt=dt, n=n, mode=mode, renorm=renorm, fuse=fuse)
 
 
 @pytest.mark.parametrize("i", range(16))
@@ -220,7 +221,7 @@ def test_random_configurations_full_parity(oracle, runner, i):
     d = synth.make_inputs(s, seed=i)
     r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], s.k, s.capacity_factor, c["n"],
                           gate_bias=d.get("gate_bias"), renormalize=bool(c["renorm"]))
-    g = runner.run_layer_step(s, d, c["n"], c["mode"], gate_renormalize=c["renorm"])
+    g = runner.run_layer_step(s, d, c["n"], c["mode"], gate_renormalize=c["renorm"], fuse_gather=c["fuse"])
     _check_routing(g, r)
     names = ["y", "dx", "dW1", "dW2"]
     if np.abs(r["dWg"]).max() > 1e-12:        # one choice renormalised, or one expert: the gate gets no gradient
@@ -429,6 +430,99 @@ def test_entry_points_one_by_one_equal_the_layer_step(oracle, runner):
     for k_ in ("y", "dx", "dWg", "dW1", "dW2"):
         assert np.array_equal(got[k_], ref[k_]), k_
     _check_values(got, orc, TOL["bf16"])
+
+
+
+# ---------------------------------------------------------------------------------
+# the first expert GEMM reading its rows straight from the token-major input
+# ---------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_gathered_first_gemm_equals_dispatch_then_gemm_bit_for_bit(oracle, runner, dt):
+    """moe_slot_rows inverts the oracle's slot map exactly, and moe_expert_ffn_fwd_gather gives, on every
+    valid row, the bits that moe_dispatch followed by moe_expert_ffn_fwd gives."""
+    from paper_2506_22175_amd import binding as B
+    s = synth.custom_shape(602, 264, 328, 7, 3, 0.9, dtype=dt, x_std=1.0, w_std=0.05, name="gather")
+    d = synth.make_inputs(s, seed=11)
+    n = 2
+    orc = _oracle(oracle, s, d, n)
+    st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, n, s.dtype, 0)
+    st.upload(d)
+    cfg, i = st.cfg, st.inputs
+    dev, td = "cuda:0", (torch.bfloat16 if dt == "bf16" else torch.float32)
+    Rp = st.C_p * s.E
+    sscr = torch.empty(B.moe_slot_scratch_bytes(cfg), dtype=torch.uint8, device=dev)
+    B.moe_route(cfg, i["x"], i["Wg"], None, st.logits, st.topk_idx, st.topk_w)
+    B.moe_assign_slots(cfg, st.topk_idx, st.topk_w, st.slot, st.counts, None, sscr)
+    rows = torch.full((n, Rp), -7, dtype=torch.int32, device=dev)
+    B.moe_slot_rows(cfg, st.slot, rows)
+    torch.cuda.synchronize()
+    # the inverse map, entry by entry, from the oracle's slots
+    want = np.full((n, Rp), -7, dtype=np.int32)
+    Tp = s.T // n
+    for t in range(s.T):
+        for j in range(s.k):
+            sl = orc["slot"][t, j]
+            if sl >= 0:
+                want[t // Tp, sl] = t
+    assert np.array_equal(rows.cpu().numpy(), want)
+    assert (want >= 0).sum() == orc["counts"].sum()
+    for p in range(n):
+        out = {}
+        for kind in ("dispatched", "gathered"):
+            Z = torch.zeros((Rp, s.H), dtype=td, device=dev)
+            A = torch.zeros((Rp, s.H), dtype=td, device=dev)
+            DO = torch.zeros((Rp, s.M), dtype=td, device=dev)
+            if kind == "dispatched":
+                DI = torch.zeros((Rp, s.M), dtype=td, device=dev)
+                B.moe_dispatch(cfg, p, i["x"], st.slot, DI)
+                B.moe_expert_ffn_fwd(cfg, p, DI, st.counts, i["W1"], i["W2"], Z, A, DO)
+            else:
+                B.moe_expert_ffn_fwd_gather(cfg, p, i["x"], rows, st.counts, i["W1"], i["W2"], Z, A, DO)
+            torch.cuda.synchronize()
+            out[kind] = [runner.to_host(t_) for t_ in (Z, A, DO)]
+        valid = np.zeros(Rp, dtype=bool)
+        for e in range(s.E):
+            valid[e * st.C_p: e * st.C_p + orc["counts"][p, e]] = True
+        for a, b in zip(out["dispatched"], out["gathered"]):
+            assert np.array_equal(a[valid], b[valid])
+        assert np.abs(out["gathered"][2][valid]).max() > 0
+
+
+@pytest.mark.parametrize("mode,n", [(0, 1), (0, 4), (1, 4), (2, 2), (2, 4), (4, 4)])
+def test_layer_step_with_the_gathered_first_gemm(oracle, runner, mode, n):
+    """fuse_gather changes where the first GEMM reads from, not one bit of any result."""
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=2)
+    r = _oracle(oracle, s, d, n)
+    plain = runner.run_layer_step(s, d, n, mode)
+    fused = runner.run_layer_step(s, d, n, mode, fuse_gather=1)
+    _check_routing(fused, r)
+    _check_values(fused, r, TOL[s.dtype])
+    for k_ in ("y", "dx", "dWg", "dW1", "dW2"):
+        assert np.array_equal(fused[k_], plain[k_]), k_
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_launch_counts_with_the_gathered_first_gemm(runner, mode):
+    """Forward: two GEMMs and one permutation (the combine) per partition; backward dispatches dy and
+    T_I and runs dispatch-backward in every mode."""
+    from paper_2506_22175_amd import binding as B
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=0)
+    n = 4
+    st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, n, s.dtype, mode, fuse_gather=1)
+    st.upload(d)
+    st.zero_grads()
+    B.moe_launch_counts(reset=True)
+    st.forward()
+    torch.cuda.synchronize()
+    g, p, _ = B.moe_launch_counts(reset=True)
+    assert (g, p) == (2 * n, n)
+    st.backward()
+    torch.cuda.synchronize()
+    g, p, _ = B.moe_launch_counts(reset=True)
+    assert (g, p) == ((5 if mode == 2 else 4) * n, 3 * n)
 
 
 def test_kernel_timing_hooks_see_every_gemm(runner):
