@@ -59,7 +59,7 @@ def recorded_traffic(workload, n, reuse):
     return None
 
 
-def measure(args, workload, n, reuse, steps, warmup, brief=False):
+def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0):
     """Time `steps` whole layer steps of one workload; returns the result dict and the inputs."""
     import numpy as np
     import torch
@@ -70,7 +70,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
     inp = synth.make_inputs(shape, seed=0)
     st = runner.LayerState(shape.T, shape.M, shape.H, shape.E, shape.k, shape.capacity_factor, n,
                            shape.dtype, reuse, second_stream=not args.single_stream,
-                           grad_overwrite=0 if args.accumulate else 1)
+                           grad_overwrite=0 if args.accumulate else 1, fuse_gather=fuse)
     st.upload(inp)
     st.zero_grads()
     torch.cuda.reset_peak_memory_stats()
@@ -142,7 +142,8 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
                 "kernel_timing": kernel_timing}
 
     # HBM-bound permutations: algorithmic bytes = rows read + rows written
-    n_disp_per_step = 1 + (2 if (reuse in (1, 2, 4) and n > 2) else 1)   # x forward; dy (+ x again when T_DI buffers are shared) backward
+    # x forward (not with the gathered first GEMM); dy backward, and x again when T_DI is not where forward left it
+    n_disp_per_step = (0 if fuse else 1) + (2 if (fuse or (reuse in (1, 2, 4) and n > 2)) else 1)
     # dispatch reads every token row once, however many experts it goes to, and writes the kept rows
     # (counting a read per kept row, 2*R rows, would flatter the kernel by a quarter at k = 2)
     bytes_dispatch = (R + T) * M * es + T * k * 4.0         # per dispatch of all partitions
@@ -240,7 +241,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
         "data": "synthetic",
         "config": {"workload": f"{shape.name}: T={T} M={M} H={H} E={shape.E} k={k} cf={shape.capacity_factor}",
                    "n_partitions": n, "reuse_mode": reuse, "streams": 1 if args.single_stream else 2,
-                   "hip_graph": bool(args.graph),
+                   "hip_graph": bool(args.graph), "fuse_gather": int(fuse),
                    "weight_grads": "accumulated into zeroed buffers" if args.accumulate else "overwritten each step",
                    "kept_rows": R, "drop_rate": drop_rate},
         "tflops_model": flop_model / (ms_per_step * 1e-3) / 1e12,
@@ -258,7 +259,8 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False):
                          "GPUs (8 DGX A100); ratios on other hardware, not a target for this number",
     }
     if brief:
-        out = {"workload": out["config"]["workload"], "n_partitions": n, "reuse_mode": reuse, "tokens_per_s": out["value"],
+        out = {"workload": out["config"]["workload"], "n_partitions": n, "reuse_mode": reuse, "fuse_gather": int(fuse),
+               "tokens_per_s": out["value"],
                "ms_per_step": out["ms_per_step"], "tflops_executed": out["tflops_executed"],
                "gemm_tflops": roofline["achieved"], "gemm_frac_of_peak": roofline["frac"],
                "drop_rate": drop_rate, "workspace_bytes": mem[f"mode{reuse}"]["workspace"]}
@@ -319,11 +321,14 @@ def main():
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="no HIP events around the kernels in the timed region (roofline fields are then empty)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--fuse-gather", action="store_true",
+                    help="the first expert GEMM gathers its rows from the token-major input (no forward dispatch)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
-    out, shape, inp = measure(args, args.workload, args.n, args.reuse, args.steps, args.warmup)
+    out, shape, inp = measure(args, args.workload, args.n, args.reuse, args.steps, args.warmup,
+                              fuse=1 if args.fuse_gather else 0)
     if not args.no_sweep:
         # the other workloads of the set, a few steps each, for the record
         others = []
@@ -334,6 +339,9 @@ def main():
                 continue
             o, _, _ = measure(args, wl, n, mode, 5, 2, brief=True)
             others.append(o)
+        # the same configuration with the other setting of the gathered first GEMM
+        o, _, _ = measure(args, args.workload, args.n, args.reuse, 10, 3, brief=True, fuse=0 if args.fuse_gather else 1)
+        out["gathered_first_gemm"] = {"this_run": int(args.fuse_gather), "other_setting": o}
         out["other_workloads"] = others
         # measured step of every strategy of Table II beside Eq. 10's prediction
         names = {0: "none", 2: "S4", 3: "S1", 4: "S2", 5: "S3"}

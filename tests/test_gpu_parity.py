@@ -300,13 +300,13 @@ def test_grad_overwrite_equals_accumulation_from_zero(runner, case):
 # the large workloads: routing on everything, values on samples
 # ---------------------------------------------------------------------------------
 
-def _sampled_check(oracle, runner, s, n, mode, seed=0, n_tokens=64, n_cols=4, grad_overwrite=0):
+def _sampled_check(oracle, runner, s, n, mode, seed=0, n_tokens=64, n_cols=4, grad_overwrite=0, fuse_gather=0):
     d = synth.make_inputs(s, seed=seed)
     logits, p, idx, w = oracle.route(d["x"], d["Wg"], s.k, d.get("gate_bias"))
     C_p = oracle.capacity(s.T, s.E, s.k, s.capacity_factor, n)
     slot, counts = oracle.assign_slots(idx, s.E, C_p, n)
     r = dict(logits=logits, idx=idx, w=w, slot=slot, counts=counts, C_p=C_p)
-    g = runner.run_layer_step(s, d, n, mode, grad_overwrite=grad_overwrite)
+    g = runner.run_layer_step(s, d, n, mode, grad_overwrite=grad_overwrite, fuse_gather=fuse_gather)
     _check_routing(g, r)
     rng = np.random.default_rng(seed + 100)
     toks = rng.choice(s.T, size=n_tokens, replace=False)
@@ -351,11 +351,13 @@ def test_skewed_workload_sampled(oracle, runner):
     assert r["counts"].max() == r["C_p"]         # and fills the popular experts to capacity
 
 
-@pytest.mark.parametrize("n", [2, 4, 8])
-def test_large_workload_sampled_in_bench_configuration(oracle, runner, n):
+@pytest.mark.parametrize("n,fuse", [(2, 0), (4, 1), (8, 0)])
+def test_large_workload_sampled_in_bench_configuration(oracle, runner, n, fuse):
     """The shape and launch configuration bench.py times (n = 2: two streams, buffers shared and T_M
-    recomputed, weight gradients stored by the first partition), and the workload's other partition counts."""
-    _sampled_check(oracle, runner, synth.WORKLOADS["large"], n, 2, n_tokens=48 if n == 2 else 24, grad_overwrite=1)
+    recomputed, weight gradients stored by the first partition), and the workload's other partition
+    counts, one of them with the first GEMM gathering its rows from the token-major input."""
+    _sampled_check(oracle, runner, synth.WORKLOADS["large"], n, 2, n_tokens=48 if n == 2 else 24, grad_overwrite=1,
+                   fuse_gather=fuse)
 
 
 # ---------------------------------------------------------------------------------
