@@ -231,6 +231,39 @@ def test_random_configurations_full_parity(oracle, runner, i):
     _check_values(g, r, TOL[c["dt"]], names=tuple(names))
 
 
+def _random_larger_case(i):
+    rng = np.random.default_rng(5000 + i)
+    dt = "bf16" if i % 4 else "f32"
+    n = int(rng.choice([1, 2, 3, 4, 8]))
+    T = n * int(rng.integers(100, 700))
+    M = 8 * int(rng.integers(16, 330 if dt == "bf16" else 80))
+    H = 8 * int(rng.integers(16, 200 if dt == "bf16" else 60))
+    E = int(rng.integers(1, 17))
+    k = int(rng.integers(1, min(4, E) + 1))
+    cf = float(rng.choice([0.5, 1.0, 1.25, 2.0]))
+    mode = int(rng.integers(0, 6))
+    renorm = int(rng.integers(0, 2))
+    fuse = int(rng.integers(0, 2)) if mode not in (3, 5) else 0
+    return dict(T=T, M=M, H=H, E=E, k=k, cf=cf, dt=dt, n=n, mode=mode, renorm=renorm, fuse=fuse)
+
+
+@pytest.mark.parametrize("i", range(10))
+def test_random_larger_configurations_full_parity(oracle, runner, i):
+    """As above with shapes that span several 256-wide tiles in every dimension, ragged tails included."""
+    c = _random_larger_case(i)
+    s = synth.custom_shape(c["T"], c["M"], c["H"], c["E"], c["k"], c["cf"], dtype=c["dt"], x_std=1.0, w_std=0.05,
+                           name=f"larger{i}")
+    d = synth.make_inputs(s, seed=i)
+    r = oracle.layer_step(d["x"], d["Wg"], d["W1"], d["W2"], d["dy"], s.k, s.capacity_factor, c["n"],
+                          gate_bias=d.get("gate_bias"), renormalize=bool(c["renorm"]))
+    g = runner.run_layer_step(s, d, c["n"], c["mode"], gate_renormalize=c["renorm"], fuse_gather=c["fuse"])
+    _check_routing(g, r)
+    names = ["y", "dx", "dW1", "dW2"]
+    if np.abs(r["dWg"]).max() > 1e-12:
+        names.append("dWg")
+    _check_values(g, r, TOL[c["dt"]], names=tuple(names))
+
+
 def test_results_do_not_depend_on_streams_or_reuse_mode(runner):
     """Same kernels, same order of accumulation: one stream or two, and the three
     memory modes, give identical routing and values that agree to rounding."""
