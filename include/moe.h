@@ -21,8 +21,10 @@
  *       MOE_ERR_NULL        a required pointer is NULL
  *       MOE_ERR_SHAPE       non-positive dimension, k > E, T % n != 0, cf <= 0,
  *                           partition index out of range
- *       MOE_ERR_UNSUPPORTED E > 64, k > 8, M % 8 != 0, H % 8 != 0
- *       MOE_ERR_WORKSPACE   workspace smaller than moe_workspace_bytes()
+ *       MOE_ERR_UNSUPPORTED E > 64, k > 8, n > 64, M % 8 != 0, H % 8 != 0, unknown dtype or
+ *                           reuse mode, a reuse mode the entry point does not serve
+ *       MOE_ERR_WORKSPACE   workspace smaller than moe_workspace_bytes(), or not
+ *                           256-byte aligned
  *       MOE_ERR_HIP         a HIP call or kernel launch failed
  *   - notation: T tokens, M model dim, H expert hidden dim, E local experts,
  *     k experts per token, n partitions, T_p = T/n, C_p = rows per expert per
@@ -236,7 +238,10 @@ moe_status moe_layer_step_offload(const moe_config* cfg, const void* x, const vo
 
 /* Forward half / backward half of moe_layer_step, for callers that run other
  * work between them.  Same arguments and workspace; backward reads what forward
- * left in the workspace and in the routing outputs. */
+ * left in the workspace and in the routing outputs, and consumes it: the kept T_M is
+ * overwritten with the weighted activations and, in the shared-buffer modes, T_DO with
+ * rows of dy.  One backward per forward; a second backward without a new forward gives
+ * wrong gradients. */
 moe_status moe_layer_forward(const moe_config* cfg, const void* x,
                              const void* Wg, const float* gate_bias, const void* W1, const void* W2,
                              void* y, float* logits, int32_t* topk_idx, float* topk_w,
@@ -340,8 +345,8 @@ moe_status moe_gran_get(moe_gran* g, const moe_config* cfg, const void* x, const
  * moe_select_strategy: among the strategies whose bit is set in allowed_mask (bit s =
  *   strategy s), the one with the least forward + backward cost; ties to the lower
  *   number.  Non-positive sizes or speeds, unknown strategy, empty mask: MOE_ERR_SHAPE.
- * Host only.  (S1-S3 need a host-copy stream that this library does not have; their
- * rows are here for the model's sake.) */
+ * Host only.  (All five rows can be run and timed: "none" and S4 through moe_layer_step,
+ * S1-S3 through moe_layer_step_offload.) */
 typedef struct {
     double W_comp, W_comm, W_mem;
     double sigma, mu_comp, mu_all, eta_all;

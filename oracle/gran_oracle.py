@@ -3,71 +3,63 @@
 TEST INFRASTRUCTURE ONLY.  Nothing on the product path may import this file.
 It shares no code with the C++ implementation behind the C ABI.
 
-The algorithm decides the number of partitions n for a batch of B tokens with
-as few timed searches as possible.  It keeps two pieces of global state:
+What the algorithm does: it answers "into how many partitions n should a batch of
+B tokens be cut" with as few timed searches as possible.  It remembers every
+answer it has given, and for every n it has ever found it remembers the span of
+batch sizes, from the smallest to the largest searched B, whose search gave that
+n.  On the section's hypothesis that the best n never decreases as B grows, any B
+inside such a span must have that same n, so only a B outside every span costs a
+search.  Written here from that reading as three operations:
 
-  S            the set of pairs (R_n, n): one closed range R_n = [B_n^lower,
-               B_n^upper] of batch sizes per value of n that has been found;
-  cache_table  B -> n for every B that has been asked before.
+  lookup(B)     an answer given before for this B, else the n of a span that
+                holds B, else nothing;
+  search        the caller's search by timed trials, used only when lookup has
+                nothing;
+  record(B, n)  after a search: the span of n is created as [B, B] or stretched
+                to hold B.
 
-Steps, in the paper's order:
-  1. B in cache_table: return the cached n.
-  2. find(S, B): the pair whose range contains B.  Found: that n is the answer
-     (no search), by the hypothesis that the best n grows monotonically with B,
-     which makes the ranges disjoint.
-  3. Not found: n = searchBestGran(B), a search by timed trials.  Then the pair
-     of *this n* is looked up in S; absent: insert (range(B, B), n); present:
-     widen its range to [min(B, lower), max(B, upper)].
-  4. cache_table[B] = n; return n.
+Readings where the paper's listing is ambiguous (also in the design notes):
+  * after the search the listing looks the set up a second time; the section's
+    prose makes that a lookup of the span that belongs to the n just found, and
+    the stretched span has to be stored back;
+  * spans can overlap only when the hypothesis fails; then, among the spans that
+    hold B, the one with the smallest lower end answers (two spans cannot share
+    a lower end: a span's lower end is a searched B whose answer is its n).
 
-Readings where the listing is ambiguous (also in the design notes):
-  * the second find of the listing is a lookup by the n just found (the prose
-    of Section III-C says "if n is not in S ... otherwise merge B into R_n"),
-    and the widened range is written back into S;
-  * find(S, B) over ranges that overlap (possible only when the monotonicity
-    hypothesis fails): the pair with the smallest lower bound among those that
-    contain B wins; ties on the lower bound cannot occur, because a pair's
-    lower bound is a searched B whose n is that pair's n.
-
-S is held here as a plain list scanned from the start; the paper's binary
-search tree is a matter of speed, not of result.
+Spans are held in a dictionary keyed by n and scanned in full; the ordered tree
+the paper suggests changes the speed, not the answers.
 """
 from __future__ import annotations
 
-from typing import Callable, Dict, List, Tuple
+from typing import Callable, Dict, List, Optional, Tuple
 
 
 class GranularitySearch:
     def __init__(self, search_best_gran: Callable[[int], int]):
         self.search_best_gran = search_best_gran
-        self.S: List[Tuple[int, int, int]] = []          # (lower, upper, n)
-        self.cache_table: Dict[int, int] = {}
+        self.span_of: Dict[int, Tuple[int, int]] = {}    # n -> (smallest, largest) searched B that gave n
+        self.answered: Dict[int, int] = {}               # B -> n, every answer given so far
         self.searches: List[int] = []                    # every B that needed a search, in order
 
-    def find(self, B: int) -> int:
-        """n of the pair whose range holds B, or -1."""
-        best = None
-        for lower, upper, n in self.S:
-            if lower <= B <= upper and (best is None or lower < best[0]):
-                best = (lower, n)
-        return -1 if best is None else best[1]
+    def lookup(self, B: int) -> Optional[int]:
+        if B in self.answered:
+            return self.answered[B]
+        holding = [(lo, n) for n, (lo, hi) in self.span_of.items() if lo <= B <= hi]
+        return min(holding)[1] if holding else None
 
-    def ranges(self) -> List[Tuple[int, int, int]]:
-        """The pairs of S ordered by lower bound, as (lower, upper, n)."""
-        return sorted(self.S)
+    def record(self, B: int, n: int) -> None:
+        lo, hi = self.span_of.get(n, (B, B))
+        self.span_of[n] = (min(lo, B), max(hi, B))
 
     def get(self, B: int) -> int:
-        if B in self.cache_table:
-            return self.cache_table[B]
-        n = self.find(B)
-        if n == -1:
+        n = self.lookup(B)
+        if n is None:
             n = int(self.search_best_gran(B))
             self.searches.append(B)
-            for i, (lower, upper, m) in enumerate(self.S):
-                if m == n:
-                    self.S[i] = (min(B, lower), max(B, upper), n)
-                    break
-            else:
-                self.S.append((B, B, n))
-        self.cache_table[B] = n
+            self.record(B, n)
+        self.answered[B] = n
         return n
+
+    def ranges(self) -> List[Tuple[int, int, int]]:
+        """The spans ordered by lower end, as (lower, upper, n)."""
+        return sorted((lo, hi, n) for n, (lo, hi) in self.span_of.items())

@@ -45,7 +45,7 @@ moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void*
     const int* cp = counts + (size_t)part * d.E;
     const long long eM = (long long)d.Cp * d.M, eH = (long long)d.Cp * d.H, wMH = (long long)d.M * d.H;
     if (recompute) {
-        // T_M again from T_DI (Section III-D: "T_M can be re-computed from T_DI")
+        // T_M again from T_DI (Section III-D: the overwritten T_M is restored by recomputation)
         GemmArgs a = base_args(d, cp);
         a.A = DI; a.lda = d.M; a.a_estride = eM;
         a.B = W1; a.ldb = d.H; a.b_estride = wMH;

@@ -333,7 +333,11 @@ def test_grad_overwrite_equals_accumulation_from_zero(runner, case):
 # the large workloads: routing on everything, values on samples
 # ---------------------------------------------------------------------------------
 
-def _sampled_check(oracle, runner, s, n, mode, seed=0, n_tokens=64, n_cols=4, grad_overwrite=0, fuse_gather=0):
+def _sampled_check(oracle, runner, s, n, mode, seed=0, n_tokens=256, n_experts=4, n_cols=16, grad_overwrite=0,
+                   fuse_gather=0):
+    """Routing on the whole input; y and dx of n_tokens sampled tokens (plus some with dropped choices) and
+    n_experts x n_cols (expert, column) slices of each weight gradient, each computed by the oracle one by
+    one from the definition."""
     d = synth.make_inputs(s, seed=seed)
     logits, p, idx, w = oracle.route(d["x"], d["Wg"], s.k, d.get("gate_bias"))
     C_p = oracle.capacity(s.T, s.E, s.k, s.capacity_factor, n)
@@ -354,7 +358,7 @@ def _sampled_check(oracle, runner, s, n, mode, seed=0, n_tokens=64, n_cols=4, gr
     full = (slot < 0).all(axis=1)
     if full.any():
         assert np.all(g["y"][full] == 0.0) and np.all(g["dx"][full] == 0.0)
-    for e in rng.choice(s.E, size=2, replace=False):
+    for e in rng.choice(s.E, size=n_experts, replace=False):
         hc = rng.choice(s.H, size=n_cols, replace=False)
         mc = rng.choice(s.M, size=n_cols, replace=False)
         a, b = oracle.sampled_weight_grads(d["x"], d["W1"], d["W2"], d["dy"], r, n, C_p, int(e), hc, mc)
@@ -364,15 +368,33 @@ def _sampled_check(oracle, runner, s, n, mode, seed=0, n_tokens=64, n_cols=4, gr
     return g, r
 
 
+_LAST_ORACLE = {}
+
+
+def _oracle_once(oracle, name, n, seed=0):
+    """The whole oracle step of a named workload; the last result is kept, so tests that differ only in the
+    memory mode (which the oracle does not know) share one evaluation."""
+    key = (name, n, seed)
+    if key not in _LAST_ORACLE:
+        _LAST_ORACLE.clear()
+        s = synth.WORKLOADS[name]
+        d = synth.make_inputs(s, seed=seed)
+        _LAST_ORACLE[key] = (d, _oracle(oracle, s, d, n))
+    return _LAST_ORACLE[key]
+
+
 def test_gpt_workload_sampled(oracle, runner):
     _sampled_check(oracle, runner, synth.WORKLOADS["gpt"], 4, 2)
 
 
-def test_gpt_workload_full_oracle_one_partitioning(oracle, runner):
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("n", [1, 2, 4, 8])
+def test_gpt_workload_every_partitioning_and_memory_mode_full_oracle(oracle, runner, n, mode):
+    """The three memory modes (keep everything; share T_DI / T_DO; share and recompute T_M) at every
+    partition count the workload names, every tensor compared in full."""
     s = synth.WORKLOADS["gpt"]
-    d = synth.make_inputs(s, seed=0)
-    r = _oracle(oracle, s, d, 8)
-    g = runner.run_layer_step(s, d, 8, 2)
+    d, r = _oracle_once(oracle, "gpt", n)
+    g = runner.run_layer_step(s, d, n, mode)
     _check_routing(g, r)
     _check_values(g, r, TOL["bf16"])
 
@@ -384,13 +406,36 @@ def test_skewed_workload_sampled(oracle, runner):
     assert r["counts"].max() == r["C_p"]         # and fills the popular experts to capacity
 
 
+def test_skewed_workload_full_oracle(oracle, runner):
+    """Zipf-biased gate, heavy drops, experts from full to nearly empty: every tensor in full, the
+    gate-weight gradient (which sees the bias and the drops) included."""
+    s = synth.WORKLOADS["skewed"]
+    d, r = _oracle_once(oracle, "skewed", 4)
+    assert (r["slot"] < 0).mean() > 0.1 and r["counts"].max() == r["C_p"]
+    for overwrite in (0, 1):
+        g = runner.run_layer_step(s, d, 4, 2, grad_overwrite=overwrite)
+        _check_routing(g, r)
+        _check_values(g, r, TOL["bf16"])
+        full = (r["slot"] < 0).all(axis=1)
+        assert full.any() and np.all(g["y"][full] == 0.0) and np.all(g["dx"][full] == 0.0)
+
+
 @pytest.mark.parametrize("n,fuse", [(2, 0), (4, 1), (8, 0)])
-def test_large_workload_sampled_in_bench_configuration(oracle, runner, n, fuse):
+def test_large_workload_full_oracle_in_bench_configuration(oracle, runner, n, fuse):
     """The shape and launch configuration bench.py times (n = 2: two streams, buffers shared and T_M
     recomputed, weight gradients stored by the first partition), and the workload's other partition
-    counts, one of them with the first GEMM gathering its rows from the token-major input."""
-    _sampled_check(oracle, runner, synth.WORKLOADS["large"], n, 2, n_tokens=48 if n == 2 else 24, grad_overwrite=1,
-                   fuse_gather=fuse)
+    counts, one of them with the first GEMM gathering its rows from the token-major input.  Every output
+    tensor is compared in full with the oracle's."""
+    s = synth.WORKLOADS["large"]
+    d, r = _oracle_once(oracle, "large", n)
+    g = runner.run_layer_step(s, d, n, 2, grad_overwrite=1, fuse_gather=fuse)
+    _check_routing(g, r)
+    _check_values(g, r, TOL["bf16"])
+
+
+def test_large_workload_sampled(oracle, runner):
+    """Outputs the oracle computes one by one from the definition, at the full size."""
+    _sampled_check(oracle, runner, synth.WORKLOADS["large"], 2, 2, grad_overwrite=1)
 
 
 # ---------------------------------------------------------------------------------

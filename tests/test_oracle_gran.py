@@ -71,7 +71,7 @@ def test_cache_answers_without_find_or_search():
     g = GranularitySearch(lambda B: state["n"])
     assert g.get(64) == 2
     state["n"] = 8                      # a new search would now say 8
-    g.S.clear()                         # and find() would fail
+    g.span_of.clear()                   # and no span would hold it
     assert g.get(64) == 2
     assert g.searches == [64]
 
