@@ -132,6 +132,20 @@ moe_status moe_assign_slots(const moe_config* cfg, const int32_t* topk_idx, cons
                             void* scratch, void* stream);
 moe_status moe_slot_scratch_bytes(const moe_config* cfg, size_t* bytes);
 
+/* moe_assign_slots for callers that cannot allocate device memory or size a scratch
+ * buffer themselves (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): same arguments without `scratch`, same results bit for bit.  The
+ * histograms live in a 256 KiB array that the library holds on every GPU it runs on
+ * until the process ends; the call allocates and frees nothing.
+ *   moe_slot_scratch_bytes(cfg) > 256 KiB (that is n*k*ceil(T_p/1024)*E > 65536):
+ *   MOE_ERR_WORKSPACE, nothing is launched.
+ *   The first call on a device looks up the array's address on that device (make it
+ *   outside stream capture).  Every call on a GPU uses that GPU's one array: calls
+ *   that overlap in time on one GPU (different streams, or graphs replayed side by
+ *   side) race; serialise them.  Nothing needs clearing between calls. */
+moe_status moe_assign_slots_static(const moe_config* cfg, const int32_t* topk_idx, const float* topk_w,
+                                   int32_t* slot, int32_t* counts, float* slot_w, void* stream);
+
 /* Dispatch S of partition `part` (Fig. 1: T_I -> T_DI; on one GPU the All-to-All
  * is a local permutation): DI[slot[t,j]] = src[t] for every kept (t, j) of the
  * partition's tokens.  src [T,M] (x, or dy in backward); DI [R_p,M] out.

@@ -20,7 +20,7 @@ MOE_REUSE_NONE, MOE_REUSE_BUFFERS, MOE_REUSE_RECOMPUTE = 0, 1, 2
 MOE_REUSE_S1, MOE_REUSE_S2, MOE_REUSE_S3 = 3, 4, 5
 
 EXPORTS = [
-    "moe_capacity", "moe_workspace_bytes", "moe_route", "moe_assign_slots", "moe_slot_scratch_bytes",
+    "moe_capacity", "moe_workspace_bytes", "moe_route", "moe_assign_slots", "moe_assign_slots_static", "moe_slot_scratch_bytes",
     "moe_dispatch", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_dw_parts", "moe_combine",
     "moe_slot_rows", "moe_expert_ffn_fwd_gather",
     "moe_gate_bwd", "moe_gate_scratch_bytes", "moe_dispatch_bwd", "moe_layer_step",
@@ -165,6 +165,11 @@ def moe_route(cfg, x, Wg, gate_bias, logits, topk_idx, topk_w, stream=None):
 def moe_assign_slots(cfg, topk_idx, topk_w, slot, counts, slot_w, scratch, stream=None):
     _check(lib().moe_assign_slots(_cfg(cfg), _p(topk_idx), _p(topk_w), _p(slot), _p(counts), _p(slot_w),
                                   _p(scratch), _s(stream)), "moe_assign_slots")
+
+
+def moe_assign_slots_static(cfg, topk_idx, topk_w, slot, counts, slot_w, stream=None):
+    _check(lib().moe_assign_slots_static(_cfg(cfg), _p(topk_idx), _p(topk_w), _p(slot), _p(counts), _p(slot_w),
+                                         _s(stream)), "moe_assign_slots_static")
 
 
 def moe_dispatch(cfg, part, src, slot, DI, dO_saved=None, dw=None, stream=None):

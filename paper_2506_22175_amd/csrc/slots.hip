@@ -102,6 +102,46 @@ extern "C" moe_status moe_slot_scratch_bytes(const moe_config* cfg, size_t* byte
     return MOE_OK;
 }
 
+namespace moe {
+
+static moe_status assign_slots(const Dims& d, const int32_t* topk_idx, const float* topk_w, int32_t* slot,
+                               int32_t* counts, float* slot_w, int* hist, hipStream_t s) {
+    const int nb = (d.Tp + SLOT_BLOCK - 1) / SLOT_BLOCK;
+    dim3 grid(nb, d.k, d.n);
+    ProfScope ps(PK_SLOTS, s);
+    hipLaunchKernelGGL(slot_hist_kernel, grid, dim3(SLOT_BLOCK), 0, s, topk_idx, hist, d.Tp, d.k, d.E, nb);
+    MOE_CHECK_LAUNCH();
+    hipLaunchKernelGGL(slot_assign_kernel, grid, dim3(SLOT_BLOCK), 0, s, topk_idx, topk_w, (const int*)hist, slot,
+                       counts, slot_w, d.Tp, d.k, d.E, nb, d.Cp);
+    count_launch(LC_OTHER, 2);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+
+// Histogram memory of moe_assign_slots_static: one array per GPU, resident for the life of the
+// process.  In host code this name is only a handle for hipGetSymbolAddress; the device address
+// it yields (one per device) is what kernels are given.
+constexpr size_t STATIC_SCRATCH_BYTES = 256 * 1024;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_static_scratch[MAX_DEVICES];
+
+static moe_status static_scratch(void** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return MOE_ERR_UNSUPPORTED;
+    if (!g_static_scratch[dev]) {
+        void* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return MOE_ERR_HIP;
+        g_static_scratch[dev] = ptr;
+    }
+    *out = g_static_scratch[dev];
+    return MOE_OK;
+}
+
+}  // namespace moe
+
 extern "C" moe_status moe_assign_slots(const moe_config* cfg, const int32_t* topk_idx, const float* topk_w,
                                        int32_t* slot, int32_t* counts, float* slot_w,
                                        void* scratch, void* stream) {
@@ -109,17 +149,21 @@ extern "C" moe_status moe_assign_slots(const moe_config* cfg, const int32_t* top
     MOE_TRY(moe::make_dims(cfg, &d));
     if (!topk_idx || !slot || !counts || !scratch) return MOE_ERR_NULL;
     if (slot_w && !topk_w) return MOE_ERR_NULL;
-    hipStream_t s = (hipStream_t)stream;
-    int nb = (d.Tp + moe::SLOT_BLOCK - 1) / moe::SLOT_BLOCK;
-    dim3 grid(nb, d.k, d.n);
-    moe::ProfScope ps(moe::PK_SLOTS, s);
-    hipLaunchKernelGGL(moe::slot_hist_kernel, grid, dim3(moe::SLOT_BLOCK), 0, s,
-                       topk_idx, (int*)scratch, d.Tp, d.k, d.E, nb);
-    MOE_CHECK_LAUNCH();
-    hipLaunchKernelGGL(moe::slot_assign_kernel, grid, dim3(moe::SLOT_BLOCK), 0, s,
-                       topk_idx, topk_w, (const int*)scratch, slot, counts, slot_w,
-                       d.Tp, d.k, d.E, nb, d.Cp);
-    moe::count_launch(moe::LC_OTHER, 2);
-    MOE_CHECK_LAUNCH();
-    return MOE_OK;
+    return moe::assign_slots(d, topk_idx, topk_w, slot, counts, slot_w, (int*)scratch, (hipStream_t)stream);
+}
+
+extern "C" moe_status moe_assign_slots_static(const moe_config* cfg, const int32_t* topk_idx, const float* topk_w,
+                                              int32_t* slot, int32_t* counts, float* slot_w, void* stream) {
+    moe::Dims d;
+    MOE_TRY(moe::make_dims(cfg, &d));
+    if (!topk_idx || !slot || !counts) return MOE_ERR_NULL;
+    if (slot_w && !topk_w) return MOE_ERR_NULL;
+    size_t need = 0;
+    MOE_TRY(moe_slot_scratch_bytes(cfg, &need));
+    if (need > moe::STATIC_SCRATCH_BYTES) return MOE_ERR_WORKSPACE;
+    void* hist = nullptr;
+    MOE_TRY(moe::static_scratch(&hist));
+    // every histogram entry the ranking kernel reads is written by the histogram kernel of the same
+    // call, so nothing of an earlier call's contents has to be cleared
+    return moe::assign_slots(d, topk_idx, topk_w, slot, counts, slot_w, (int*)hist, (hipStream_t)stream);
 }
