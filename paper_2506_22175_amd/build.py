@@ -22,9 +22,6 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.jo
          "-Wno-unused-command-line-argument"]
 
 
-EXTRA = os.environ.get("MOE_HIPCC_FLAGS", "").split()      # e.g. -DMOE_GEMM_CFG=2 for experiments
-
-
 def _compile(src: str, force: bool) -> str:
     bdir = os.path.join(HERE, "_build")
     os.makedirs(bdir, exist_ok=True)
@@ -34,7 +31,7 @@ def _compile(src: str, force: bool) -> str:
     deps.append(os.path.join(ROOT, "include", "moe.h"))
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(p) for p in deps):
         return obj
-    r = subprocess.run(["hipcc", *FLAGS, *EXTRA, "-c", srcp, "-o", obj], capture_output=True, text=True)
+    r = subprocess.run(["hipcc", *FLAGS, "-c", srcp, "-o", obj], capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                      if "packed-fp32-ops" not in l)          # host pass does not know the feature
     if r.returncode != 0:

@@ -51,33 +51,44 @@ __device__ __forceinline__ v4i make_rsrc(const void* p, unsigned bytes) {
 // every transposing LDS read wait for all of them (vmcnt(0)), which serialises the
 // ring.  The kernel waits with explicit s_waitcnt vmcnt(N) before each barrier instead.
 __device__ __forceinline__ void load_to_lds(v4i rsrc, unsigned lds_off, unsigned voff) {
-    unsigned saved_m0;
-    asm volatile("s_mov_b32 %0, m0\n\t"
-                 "s_mov_b32 m0, %1\n\t"
+    // m0 carries the LDS address of the load and nothing else in these kernels (no LDS-direct reads, no
+    // relative register indexing, no message sends), so it is not saved and restored around the load
+    asm volatile("s_mov_b32 m0, %0\n\t"
                  "s_nop 0\n\t"
-                 "buffer_load_dwordx4 %2, %3, 0 offen lds\n\t"
-                 "s_mov_b32 m0, %0"
-                 : "=&s"(saved_m0) : "s"(lds_off), "v"(voff), "s"(rsrc) : "memory");
+                 "buffer_load_dwordx4 %1, %2, 0 offen lds"
+                 : : "s"(lds_off), "v"(voff), "s"(rsrc) : "memory");
 }
 __device__ __forceinline__ unsigned lds_address(const char* p) {
     return (unsigned)(unsigned long long)(__attribute__((address_space(3))) const char*)p;
 }
 
 // ---- tile shape ------------------------------------------------------------------
-template <int BM_, int BN_, int BK_, int NS_, int WAVES_M_, int WAVES_N_, int OCC_>
+// Three main loops:
+//   LOOP_RING2  ring of two stages, compiler-scheduled;
+//   LOOP_PIPE32 ring of five stages of 32 k, hand-scheduled (one or two waves per SIMD);
+//   LOOP_W64    hand-scheduled 64-k steps with one ring per operand: a K-contiguous operand
+//               travels as whole 128-byte lines (units of 64 k), the other one in tiles of 32 k.
+enum { LOOP_RING2 = 0, LOOP_PIPE32 = 1, LOOP_W64 = 2 };
+template <int BM_, int BN_, int BK_, int NS_, int WAVES_M_, int WAVES_N_, int OCC_, int LOOP_>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, NS = NS_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
-    static constexpr int OCC = OCC_;
+    static constexpr int OCC = OCC_, LOOP = LOOP_;
     static constexpr int WAVES = WAVES_M * WAVES_N;
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     static constexpr int TM = WM / 32, TN = WN / 32;
     static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
-    static constexpr int LDS_BYTES = NS * STAGE_BYTES;
-    // one wave per SIMD: the main loop is written out instruction by instruction
-    static constexpr bool PIPE = (BK == 32 && NS == 5);
+    static constexpr int LDS_BYTES = LOOP == LOOP_W64 ? 160 * 1024 : NS * STAGE_BYTES;
+    static constexpr bool PIPE = LOOP == LOOP_PIPE32;
+    // columns of a wave's block that pass through the staging region at a time, and where that region starts
+    static constexpr int CW = LOOP == LOOP_W64 ? 64 : WN;
+    static constexpr int STAGING_OFF = LOOP == LOOP_W64 ? 64 * 1024 : 0;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds the CU's 160 KB");
     static_assert(BK == 32 || BK == 64, "tile depth");
+    static_assert(LOOP != LOOP_PIPE32 || (BK == 32 && NS == 5), "the hand-scheduled ring is five stages of 32 k");
+    static_assert(LOOP != LOOP_RING2 || NS == 2, "two stages");
+    static_assert(LOOP != LOOP_W64 || (BM == 256 && BN == 256 && BK == 64 && WAVES_M == 2 && WAVES_N == 2 && OCC == 1),
+                  "the two-ring loop is written for four waves of 128 x 128");
 };
 
 // ---- K-contiguous operand tile: R rows x BK k ---------------------------------------
@@ -134,7 +145,10 @@ struct KCTile {
     }
     __device__ __forceinline__ void load_one(char* tile, int k0, int wid, int j) const {
         const int q = wid * NI + j;
-        load_to_lds(rsrc, lds_address(tile) + q * 1024, (k0 + kc[j] < K) ? voff[j] + (unsigned)k0 * 2u : OOB_OFFSET);
+        unsigned off = voff[j] + (unsigned)k0 * 2u;
+        // only a tile that reaches beyond K (a wave-uniform condition) has lanes to switch off
+        if (k0 + BK > K) off = (k0 + kc[j] < K) ? off : OOB_OFFSET;
+        load_to_lds(rsrc, lds_address(tile) + q * 1024, off);
     }
     __device__ __forceinline__ void load(char* tile, int k0, int wid) const {
 #pragma unroll
@@ -262,19 +276,29 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int BM = C::BM, BN = C::BN, WM = C::WM, WN = C::WN, TM = C::TM, TNN = C::TN;
     constexpr int STAGE = C::STAGE_BYTES, BK = C::BK, NS = C::NS;
+    constexpr bool W64 = C::LOOP == LOOP_W64;
+    // Depth of one load unit of each operand.  In the two-ring loop a K-contiguous row operand (A of
+    // NN) or the K-contiguous weights (B of NT) travel 64 k at a time, so that every request is a whole
+    // 128-byte line; the other operand keeps tiles of 32 k.
+    constexpr bool A_WIDE = W64 && LAY == GEMM_NN;
+    constexpr int AK = W64 ? (A_WIDE ? 64 : 32) : BK, BKB = W64 ? (A_WIDE ? 32 : 64) : BK;
+    static_assert(!W64 || LAY != GEMM_TN, "both operands of the weight-gradient GEMM are N-contiguous: five stages of 32 k serve them");
     constexpr int A_BYTES = BM * BK * 2;
-    static_assert(C::PIPE || NS == 2, "ring plans below: five stages of 32 k hand-scheduled, or two stages");
     // The epilogue stages accumulators in the first SB stages of the ring; a tile's ring
     // starts at stage SB, so that its first operand tiles can arrive during the epilogue
-    // of the tile before.
+    // of the tile before.  (Two-ring loop: in the third unit of the wide ring.)
     constexpr int SB = C::PIPE ? 2 : 1;
-    static_assert(C::WAVES * 32 * WN * 4 <= SB * STAGE, "staging does not fit below the ring's first stage");
+    constexpr int CW = C::CW;
+    static_assert(W64 || C::WAVES * 32 * CW * 4 <= SB * STAGE, "staging does not fit below the ring's first stage");
+    static_assert(!W64 || C::WAVES * 32 * CW * 4 <= 32 * 1024, "staging does not fit one unit of the wide ring");
+    // two-ring LDS map: three units of 64 k x 256 rows, then four tiles of 32 k x 256 rows
+    constexpr int WIDE_UNIT = 32 * 1024, NARROW_TILE = 16 * 1024, NARROW_OFF = 3 * WIDE_UNIT;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wid / C::WAVES_N, wn = wid % C::WAVES_N;
-    typedef typename ATile<LAY, BM, C::WAVES, BK>::type AT;
-    typedef typename BTile<LAY, BN, C::WAVES, BK>::type BT;
+    typedef typename ATile<LAY, BM, C::WAVES, AK>::type AT;
+    typedef typename BTile<LAY, BN, C::WAVES, BKB>::type BT;
     constexpr int LPW = AT::NI + BT::NI;         // loads per wave per tile
     typename AT::Frag fa[TM];
     typename BT::Frag fb[TNN];
@@ -339,9 +363,36 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
         if (l < AT::NI) ta_.load_one(st, k0, wid, l);
         else tb_.load_one(st + A_BYTES, k0, wid, l - AT::NI);
     };
-    // the part of a tile's first loads that does not touch the staging stages, and the rest
+    // two-ring loop: load l of wide unit u / of narrow tile j (k0 follows from the unit number)
+    auto load_wide = [&](const AT& ta_, const BT& tb_, int slot3, int u, int l) {
+        char* dst = smem + slot3 * WIDE_UNIT;
+        if constexpr (A_WIDE) ta_.load_one(dst, u * 64, wid, l); else tb_.load_one(dst, u * 64, wid, l);
+    };
+    auto load_narrow = [&](const AT& ta_, const BT& tb_, int slot4, int j, int l) {
+        char* dst = smem + NARROW_OFF + slot4 * NARROW_TILE;
+        if constexpr (A_WIDE) tb_.load_one(dst, j * 32, wid, l); else ta_.load_one(dst, j * 32, wid, l);
+    };
+    constexpr int WL = W64 ? (A_WIDE ? AT::NI : BT::NI) : 0;       // loads per wave: one wide unit (8)
+    constexpr int NL = W64 ? (A_WIDE ? BT::NI : AT::NI) : 0;       //                 one narrow tile (4)
+    static_assert(!W64 || (WL == 8 && NL == 4), "the two-ring schedule issues two wide and two narrow loads per block");
+    // the part of a tile's first loads that does not touch the staging region, and the rest
     auto issue_early = [&](const AT& ta_, const BT& tb_) {
-        if constexpr (C::PIPE) {
+        if constexpr (W64) {
+            // what the loop expects to be on its way when it starts: wide units 0 and 1 and the first
+            // quarter of unit 2 (late: its slot is the staging region), narrow tiles 0..2 and half of tile 3
+#pragma unroll
+            for (int l = 0; l < WL; ++l) load_wide(ta_, tb_, 0, 0, l);
+#pragma unroll
+            for (int l = 0; l < NL; ++l) load_narrow(ta_, tb_, 0, 0, l);
+#pragma unroll
+            for (int l = 0; l < NL; ++l) load_narrow(ta_, tb_, 1, 1, l);
+#pragma unroll
+            for (int l = 0; l < WL; ++l) load_wide(ta_, tb_, 1, 1, l);
+#pragma unroll
+            for (int l = 0; l < NL; ++l) load_narrow(ta_, tb_, 2, 2, l);
+#pragma unroll
+            for (int l = 0; l < NL / 2; ++l) load_narrow(ta_, tb_, 3, 3, l);
+        } else if constexpr (C::PIPE) {
 #pragma unroll
             for (int s = 0; s < 3; ++s)
 #pragma unroll
@@ -352,7 +403,10 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
         }
     };
     auto issue_late = [&](const AT& ta_, const BT& tb_) {
-        if constexpr (C::PIPE) {
+        if constexpr (W64) {
+#pragma unroll
+            for (int l = 0; l < WL / 4; ++l) load_wide(ta_, tb_, 2, 2, l);
+        } else if constexpr (C::PIPE) {
 #pragma unroll
             for (int l = 0; l < LPW; ++l) request(ta_, tb_, smem, 3 * BK, l);
 #pragma unroll
@@ -380,7 +434,88 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-        if constexpr (C::PIPE) {
+        if constexpr (W64) {
+            // Hand-scheduled loop over steps of 64 k = four blocks of TM x TN matrix instructions (16 k each).
+            // While block b is multiplied, the fragments of block b+1 are read and four loads are issued, one
+            // LDS read or load per matrix instruction.  Step t reads wide unit t (slot t mod 3) and narrow
+            // tiles 2t, 2t+1 (slots mod 4).  Two barriers per step:
+            //   after block 0: every wave has read narrow tile 2t for the last time (its slot then receives
+            //           tile 2t+4), and tile 2t+1 has landed;
+            //   after block 2: every wave has read wide unit t and narrow tile 2t+1 for the last time (their
+            //           slots receive unit t+3 and tile 2t+5), and unit t+1 and tile 2t+2 have landed.
+            // Each wave issues, per step, in this order: block 0 - wide unit t+2 loads 2,3, narrow tile 2t+3
+            // loads 2,3; block 1 - unit t+2 loads 4,5, tile 2t+4 loads 0,1; block 2 - unit t+2 loads 6,7, tile
+            // 2t+4 loads 2,3; block 3 - unit t+3 loads 0,1, tile 2t+5 loads 0,1.  At either barrier the sixteen
+            // youngest loads of the wave may still be in flight; everything older is what the step needs next.
+            constexpr int MB = TM * TNN, FR = TM + TNN;
+            static_assert(FR + 7 <= MB, "one LDS read per matrix instruction, then a load after every other one");
+            if (first) wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            bf16x8 F0[FR], F1[FR];
+            // fragment f of 16-k block kk of a step: from the wide unit at wb or from the narrow tile pair at nb0, nb1
+            auto frag = [&](int f, int kk, const char* wb, const char* nb0, const char* nb1) -> bf16x8 {
+                const char* nb = kk < 2 ? nb0 : nb1;
+                if constexpr (A_WIDE) return f < TM ? fa[f].read(wb, kk) : fb[f - TM].read(nb, kk & 1);
+                else return f < TM ? fa[f].read(nb, kk & 1) : fb[f - TM].read(wb, kk);
+            };
+#pragma unroll
+            for (int f = 0; f < FR; ++f) F0[f] = frag(f, 0, smem, smem + NARROW_OFF, smem + NARROW_OFF);
+            int w3 = 0, n4 = 0;                       // slot of wide unit t, slot of narrow tile 2t
+#pragma unroll 1
+            for (int t = 0; t < KT; ++t) {
+                const int w3a = w3 == 2 ? 0 : w3 + 1, w3b = w3a == 2 ? 0 : w3a + 1;   // slots of units t+1, t+2
+                const int n4b = n4 ^ 2;                                               // slot of tile 2t+2
+                const char* wb = smem + w3 * WIDE_UNIT;
+                const char* nb0 = smem + NARROW_OFF + n4 * NARROW_TILE;
+                const char* nb1 = nb0 + NARROW_TILE;
+                const char* wb_next = smem + w3a * WIDE_UNIT;
+                const char* nb_next = smem + NARROW_OFF + n4b * NARROW_TILE;
+                // block 0
+#pragma unroll
+                for (int m = 0; m < MB; ++m) {
+                    mfma_pinned<true>(acc[m / TNN][m % TNN], F0[TM + m % TNN], F0[m / TNN]);
+                    if (m < FR) F1[m] = frag(m, 1, wb, nb0, nb1);
+                    else if (m == FR || m == FR + 2) load_wide(ta, tb, w3b, t + 2, 2 + (m - FR) / 2);
+                    else if (m == FR + 4 || m == FR + 6) load_narrow(ta, tb, n4b + 1, 2 * t + 3, 2 + (m - FR - 4) / 2);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                wait_vmcnt<16>();
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                // block 1
+#pragma unroll
+                for (int m = 0; m < MB; ++m) {
+                    mfma_pinned<true>(acc[m / TNN][m % TNN], F1[TM + m % TNN], F1[m / TNN]);
+                    if (m < FR) F0[m] = frag(m, 2, wb, nb0, nb1);
+                    else if (m == FR || m == FR + 2) load_wide(ta, tb, w3b, t + 2, 4 + (m - FR) / 2);
+                    else if (m == FR + 4 || m == FR + 6) load_narrow(ta, tb, n4, 2 * t + 4, (m - FR - 4) / 2);
+                }
+                // block 2
+#pragma unroll
+                for (int m = 0; m < MB; ++m) {
+                    mfma_pinned<true>(acc[m / TNN][m % TNN], F0[TM + m % TNN], F0[m / TNN]);
+                    if (m < FR) F1[m] = frag(m, 3, wb, nb0, nb1);
+                    else if (m == FR || m == FR + 2) load_wide(ta, tb, w3b, t + 2, 6 + (m - FR) / 2);
+                    else if (m == FR + 4 || m == FR + 6) load_narrow(ta, tb, n4, 2 * t + 4, 2 + (m - FR - 4) / 2);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                wait_vmcnt<16>();
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                // block 3
+#pragma unroll
+                for (int m = 0; m < MB; ++m) {
+                    mfma_pinned<true>(acc[m / TNN][m % TNN], F1[TM + m % TNN], F1[m / TNN]);
+                    if (m < FR) F0[m] = frag(m, 0, wb_next, nb_next, nb_next);
+                    else if (m == FR || m == FR + 2) load_wide(ta, tb, w3, t + 3, (m - FR) / 2);
+                    else if (m == FR + 4 || m == FR + 6) load_narrow(ta, tb, n4 + 1, 2 * t + 5, (m - FR - 4) / 2);
+                }
+                w3 = w3a;
+                n4 = n4b;
+            }
+            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        } else if constexpr (C::PIPE) {
             // Hand-scheduled loop (with one wave per SIMD nothing else hides a stall): every
             // LDS read and every load into LDS sits between two matrix instructions, one per
             // instruction, and the data a block of TM x TN matrix instructions needs was
@@ -396,6 +531,9 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
             constexpr int MB = TM * TNN;                 // matrix instructions per block
             constexpr int FR = TM + TNN;                 // fragments per block: A rows first, then B columns
             static_assert(LPW % 2 == 0 && FR + LPW / 2 <= MB, "one LDS read or load per matrix instruction");
+            // a load costs the wave more issue time than one matrix instruction hides: where there is room,
+            // only every other matrix instruction is followed by one
+            constexpr int LS = (FR + 2 * (LPW / 2) - 1 <= MB) ? 2 : 1;
             if (first) wait_vmcnt<3 * LPW + LPW / 2>();            // tile 0 is in (later tiles: waited for at the handover)
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
@@ -416,7 +554,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                     mfma_pinned<C::OCC == 1>(acc[m / TNN][m % TNN], F0[TM + m % TNN], F0[m / TNN]);
                     if (m < TM) F1[m] = fa[m].read(cs, 1);
                     else if (m < FR) F1[m] = fb[m - TM].read(cs + A_BYTES, 1);
-                    else if (m < FR + LPW / 2) request(ta, tb, prv, (kt + 4) * BK, LPW / 2 + m - FR);
+                    else if (m - FR < LS * (LPW / 2) && (m - FR) % LS == 0) request(ta, tb, prv, (kt + 4) * BK, LPW / 2 + (m - FR) / LS);
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave no longer reads stage t
                 wait_vmcnt<3 * LPW>();                               // its part of tile t+1 is in
@@ -427,7 +565,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                     mfma_pinned<C::OCC == 1>(acc[m / TNN][m % TNN], F1[TM + m % TNN], F1[m / TNN]);
                     if (m < TM) F0[m] = fa[m].read(nxt, 0);
                     else if (m < FR) F0[m] = fb[m - TM].read(nxt + A_BYTES, 0);
-                    else if (m < FR + LPW / 2) request(ta, tb, cs, (kt + 5) * BK, m - FR);
+                    else if (m - FR < LS * (LPW / 2) && (m - FR) % LS == 0) request(ta, tb, cs, (kt + 5) * BK, (m - FR) / LS);
                 }
                 st = stn;
             }
@@ -486,9 +624,13 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
         // row-contiguous.  They go through buffer descriptors that end after the last valid
         // row, so there is no branch: out-of-range reads give zero, out-of-range writes are
         // dropped, and all reads of a 32-row pass are issued before the arithmetic starts.
-        constexpr int CPRW = WN / 8;                 // 8-column pieces per row of the wave's block
+        // A pass moves 32 rows x CW columns of the wave's block (CW = the block's width, or 64 where the
+        // staging region is one ring unit).
+        constexpr int CPRW = CW / 8;                 // 8-column pieces per row of a pass
         constexpr int NPIECE = 32 * CPRW / 64;       // pieces per lane
-        float* stage = reinterpret_cast<float*>(smem + wid * (32 * WN * 4));
+        constexpr int NCH = WN / CW, TJ = CW / 32;   // passes per 32 rows; 32-column accumulator blocks per pass
+        constexpr int NPASS = TM * NCH;
+        float* stage = reinterpret_cast<float*>(smem + C::STAGING_OFF + wid * (32 * CW * 4));
         constexpr int CES = (EPI == EPI_ACCUM_F32 || EPI == EPI_STORE_F32) ? 4 : 2;   // bytes per output element
         const char* Cbase = (const char*)g.C + (size_t)e * g.c_estride * CES;
         const __amdgpu_buffer_rsrc_t rC = __builtin_amdgcn_make_buffer_rsrc(
@@ -498,99 +640,118 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
             const_cast<bf16_t*>(Zbase), 0, Zbase ? (unsigned)(((size_t)(Mdim - 1) * g.ldz + g.N) * 2) : 0u, 0x00020000);
         const float* wbase = g.slot_w ? g.slot_w + (size_t)e * g.Cp : nullptr;
         const int erow = lane & 31, ehalf = lane >> 5;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int j = 0; j < TNN; ++j) {
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const int cch = (j * 32 + g4 * 8 + ehalf * 4) >> 2;
-                    float4 v = make_float4(acc[i][j][g4 * 4 + 0], acc[i][j][g4 * 4 + 1], acc[i][j][g4 * 4 + 2], acc[i][j][g4 * 4 + 3]);
-                    *reinterpret_cast<float4*>(stage + erow * WN + ((cch ^ (erow & 15)) << 2)) = v;
-                }
-            }
-            // operands of this pass from memory, all requested before any is used
-            int pm[NPIECE];
-            unsigned offC[NPIECE], offZ[NPIECE];
-            uint4 zin[NPIECE];
-            float4 cin0[NPIECE], cin1[NPIECE];
-            float wrow[NPIECE];
+        // What a pass reads from memory (the pre-activation and row weight for GeLU-backward, the old
+        // sums for float accumulation) is requested one pass ahead.
+        constexpr bool READS = (EPI == EPI_DGELU || EPI == EPI_ACCUM_F32);
+        struct PassIn { uint4 zin[NPIECE]; float4 cin0[NPIECE], cin1[NPIECE]; float wrow[NPIECE]; };
+        auto piece = [&](int ps, int t, int& m, int& c8, int& row, unsigned& oC, unsigned& oZ) {
+            const int idx = lane + 64 * t;
+            row = idx / CPRW; c8 = idx % CPRW;
+            m = m0 + wm * WM + (ps / NCH) * 32 + row;
+            const int n = n0 + wn * WN + (ps % NCH) * CW + c8 * 8;
+            const bool in = n < g.N;                 // rows beyond Mdim fall outside the descriptors by themselves
+            oC = in ? (unsigned)(m * g.ldc + n) * CES : OOB_OFFSET;
+            oZ = in ? (unsigned)(m * g.ldz + n) * 2u : OOB_OFFSET;
+        };
+        auto request_pass = [&](int ps, PassIn& in) {
 #pragma unroll
             for (int t = 0; t < NPIECE; ++t) {
-                const int idx = lane + 64 * t;
-                const int row = idx / CPRW, c8 = idx % CPRW;
-                const int m = m0 + wm * WM + i * 32 + row;
-                const int n = n0 + wn * WN + c8 * 8;
-                pm[t] = m;
-                const bool in = n < g.N;             // rows beyond Mdim fall outside the descriptors by themselves
-                offC[t] = in ? (unsigned)(m * g.ldc + n) * CES : OOB_OFFSET;
-                offZ[t] = in ? (unsigned)(m * g.ldz + n) * 2u : OOB_OFFSET;
+                int m, c8, row; unsigned oC, oZ;
+                piece(ps, t, m, c8, row, oC, oZ);
                 if constexpr (EPI == EPI_DGELU) {
-                    zin[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rZ, offZ[t], 0, 0));
-                    wrow[t] = m < Mdim ? wbase[m] : 0.0f;
+                    in.zin[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rZ, oZ, 0, 0));
+                    in.wrow[t] = m < Mdim ? wbase[m] : 0.0f;
                 }
                 if constexpr (EPI == EPI_ACCUM_F32) {
-                    cin0[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, offC[t], 0, 0));
-                    cin1[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, offC[t] + 16u, 0, 0));
+                    in.cin0[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, oC, 0, 0));
+                    in.cin1[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, oC + 16u, 0, 0));
                 }
             }
+        };
+        PassIn pin[2];
+        if constexpr (READS) request_pass(0, pin[0]);
+        float dotacc[NPIECE];                        // GeLU-backward: <gelu(Z), G> of a row over the passes of its 32 rows
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            const int i = ps / NCH, ch = ps % NCH;
+#pragma unroll
+            for (int jj = 0; jj < TJ; ++jj) {
+                const int j = ch * TJ + jj;
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int cch = (jj * 32 + g4 * 8 + ehalf * 4) >> 2;
+                    float4 v = make_float4(acc[i][j][g4 * 4 + 0], acc[i][j][g4 * 4 + 1], acc[i][j][g4 * 4 + 2], acc[i][j][g4 * 4 + 3]);
+                    *reinterpret_cast<float4*>(stage + erow * CW + ((cch ^ (erow & 15)) << 2)) = v;
+                }
+            }
+            if constexpr (READS) { if (ps + 1 < NPASS) request_pass(ps + 1, pin[(ps + 1) & 1]); }
+            const PassIn& in = pin[ps & 1];
+            // all LDS reads of the pass before its arithmetic: one round trip through LDS, not one per piece
+            float4 lo[NPIECE], hi[NPIECE];
 #pragma unroll
             for (int t = 0; t < NPIECE; ++t) {
                 const int idx = lane + 64 * t;
                 const int row = idx / CPRW, c8 = idx % CPRW;
-                const float4 lo = *reinterpret_cast<const float4*>(stage + row * WN + (((2 * c8) ^ (row & 15)) << 2));
-                const float4 hi = *reinterpret_cast<const float4*>(stage + row * WN + (((2 * c8 + 1) ^ (row & 15)) << 2));
-                float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                lo[t] = *reinterpret_cast<const float4*>(stage + row * CW + (((2 * c8) ^ (row & 15)) << 2));
+                hi[t] = *reinterpret_cast<const float4*>(stage + row * CW + (((2 * c8 + 1) ^ (row & 15)) << 2));
+            }
+#pragma unroll
+            for (int t = 0; t < NPIECE; ++t) {
+                int m, c8, row; unsigned oC, oZ;
+                piece(ps, t, m, c8, row, oC, oZ);
+                float v[8] = {lo[t].x, lo[t].y, lo[t].z, lo[t].w, hi[t].x, hi[t].y, hi[t].z, hi[t].w};
                 if constexpr (EPI == EPI_STORE) {
                     uint4 o = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o), rC, offC[t], 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o), rC, oC, 0, 0);
                 } else if constexpr (EPI == EPI_GELU) {
                     float z[8], a[8];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) { z[q] = bf16_to_f32(f32_to_bf16(v[q])); a[q] = gelu_f(z[q]); }
+                    for (int q = 0; q < 8; ++q) { z[q] = bf16_to_f32(f32_to_bf16(v[q])); a[q] = gelu_fast_f(z[q]); }
                     uint4 oz = make_uint4(pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3]), pack_bf16x2(z[4], z[5]), pack_bf16x2(z[6], z[7]));
                     uint4 oa = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
-                    if (Zbase) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oz), rZ, offZ[t], 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oa), rC, offC[t], 0, 0);
+                    if (Zbase) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oz), rZ, oZ, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oa), rC, oC, 0, 0);
                 } else if constexpr (EPI == EPI_DGELU) {
                     float z[8], dz[8], a[8];
-                    Unit8::to_float(zin[t], z);
-                    const float w = wrow[t];
-                    float dot = 0.0f;
+                    Unit8::to_float(in.zin[t], z);
+                    const float w = in.wrow[t];
+                    float dot = ch == 0 ? 0.0f : dotacc[t];
 #pragma unroll
                     for (int q = 0; q < 8; ++q) {
                         float gq, dg;
-                        gelu_both_f(z[q], &gq, &dg);
+                        gelu_both_fast_f(z[q], &gq, &dg);
+                        // columns out of range read z = 0 and an accumulator of 0: nothing to add; rows out of
+                        // range are never written below
                         dot = fmaf(gq, v[q], dot);
                         a[q] = w * gq;
                         dz[q] = w * v[q] * dg;
                     }
+                    dotacc[t] = dot;
                     uint4 od = make_uint4(pack_bf16x2(dz[0], dz[1]), pack_bf16x2(dz[2], dz[3]), pack_bf16x2(dz[4], dz[5]), pack_bf16x2(dz[6], dz[7]));
                     uint4 oa = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, od), rC, offC[t], 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oa), rZ, offZ[t], 0, 0);
-                    if (g.dw_part) {
-                        // the CPRW lanes of a row are neighbours; rows and columns out of range gave zeros
-                        if (!(pm[t] < Mdim && offC[t] != OOB_OFFSET)) dot = 0.0f;
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, od), rC, oC, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, oa), rZ, oZ, 0, 0);
+                    if (g.dw_part && ch == NCH - 1) {
+                        // the CPRW lanes of a row are neighbours
 #pragma unroll
                         for (int off = CPRW / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
-                        if (c8 == 0 && pm[t] < Mdim)
-                            g.dw_part[((size_t)e * g.Cp + pm[t]) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
+                        if (c8 == 0 && m < Mdim)
+                            g.dw_part[((size_t)e * g.Cp + m) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
                     }
                 } else if constexpr (EPI == EPI_STORE_F32) {
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, lo), rC, offC[t], 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, hi), rC, offC[t] + 16u, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, lo[t]), rC, oC, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, hi[t]), rC, oC + 16u, 0, 0);
                 } else {
-                    float4 o0 = cin0[t], o1 = cin1[t];
+                    float4 o0 = in.cin0[t], o1 = in.cin1[t];
                     o0.x += v[0]; o0.y += v[1]; o0.z += v[2]; o0.w += v[3];
                     o1.x += v[4]; o1.y += v[5]; o1.z += v[6]; o1.w += v[7];
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o0), rC, offC[t], 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o1), rC, offC[t] + 16u, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o0), rC, oC, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o1), rC, oC + 16u, 0, 0);
                 }
             }
             // the next tile's first operand tiles start their trip once the first pass is through
             // (earlier, and this pass's own reads would have to wait behind them)
-            if (i == 0 && vn >= 0) issue_early(ta2, tb2);
+            if (ps == 0 && vn >= 0) issue_early(ta2, tb2);
         }
         if (vn < 0) break;
         // Everything this wave has in flight is through: the next tile's first operand tiles have
@@ -609,40 +770,25 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     }
 }
 
-// Tile shapes in use.  All cover 256 x 256 per workgroup (the L2-to-CU traffic per flop
-// that the chip can sustain asks for no less).
-//   Cfg4   four waves of 128x128, one per SIMD: reads a third less from LDS than the
-//          eight-wave shapes; wins where the loop dominates (plain stores, weight gradients).
-//   Cfg8P  eight waves of 128x64, two per SIMD, same ring and hand-scheduled loop: the second
-//          wave hides the latencies of the arithmetic-heavy GeLU epilogue (the four-wave
-//          shape is slower there), and the loop is 5 % faster than the compiler-scheduled one.
-//   Cfg8   eight waves, ring of 2 x 64 k, compiler-scheduled loop: for the GeLU-backward
-//          GEMM, whose two operands are both K-contiguous - 64 k per tile fetches whole
-//          128-byte lines of them, 32 k would fetch half lines, which costs what the better
-//          loop gains.
-// MOE_GEMM_CFG overrides the choice at build time for experiments (3: Cfg8 everywhere,
-// 6: Cfg4 everywhere, 7: Cfg8P for both GeLU epilogues).
-typedef TileCfg<256, 256, 64, 2, 2, 4, 2> Cfg8;
-typedef TileCfg<256, 256, 32, 5, 2, 2, 1> Cfg4;
-typedef TileCfg<256, 256, 32, 5, 2, 4, 2> Cfg8P;
-#ifndef MOE_GEMM_CFG
-#define MOE_GEMM_CFG 0
-#endif
-template <int EPI> struct CfgFor {
-#if MOE_GEMM_CFG == 3
-    typedef Cfg8 type;
-#else
-    typedef Cfg4 type;
-#endif
-};
-#if MOE_GEMM_CFG == 0
-template <> struct CfgFor<EPI_GELU> { typedef Cfg8P type; };
-template <> struct CfgFor<EPI_DGELU> { typedef Cfg8 type; };
-#elif MOE_GEMM_CFG == 7
-template <> struct CfgFor<EPI_GELU> { typedef Cfg8P type; };
-template <> struct CfgFor<EPI_DGELU> { typedef Cfg8P type; };
-#endif
-typedef CfgFor<EPI_DGELU>::type CfgDgelu;
+// Tile shapes in use.  Both cover 256 x 256 per workgroup with four waves of 128 x 128, one per SIMD.
+//   CfgW   two-ring loop: for every GEMM with a K-contiguous operand (NN, NT).  A request for half a
+//          128-byte line costs the L1 as much as one for a whole line, and the loop's speed follows
+//          the number of requests; here every request but those of NT's row operand is a whole line.
+//   Cfg4   ring of 5 x 32 k: the weight-gradient GEMMs (TN), whose two operands are N-contiguous
+//          and come in whole lines anyway.
+// (The loops with two waves per SIMD, hand-scheduled or compiler-scheduled, remain selectable through
+// TileCfg: their GeLU epilogues run faster, their main loops read half as much again from LDS and lose
+// more than that.)
+typedef TileCfg<256, 256, 32, 5, 2, 2, 1, LOOP_PIPE32> Cfg4;
+typedef TileCfg<256, 256, 64, 3, 2, 2, 1, LOOP_W64> CfgW;
+template <int LAY, int EPI> struct CfgFor { typedef CfgW type; };
+template <int EPI> struct CfgFor<GEMM_TN, EPI> { typedef Cfg4 type; };
+// every layout reports the row dot of the GeLU-backward epilogue in the same number of column blocks
+typedef CfgFor<GEMM_NT, EPI_DGELU>::type CfgDgelu;
+static_assert(CfgFor<GEMM_NN, EPI_DGELU>::type::WAVES_N * 256 / CfgFor<GEMM_NN, EPI_DGELU>::type::BN ==
+              CfgDgelu::WAVES_N * 256 / CfgDgelu::BN &&
+              CfgFor<GEMM_TN, EPI_DGELU>::type::WAVES_N * 256 / CfgFor<GEMM_TN, EPI_DGELU>::type::BN ==
+              CfgDgelu::WAVES_N * 256 / CfgDgelu::BN, "column blocks per 256 columns");
 
 int gemm_bf16_dw_parts(int H) { return ((H + CfgDgelu::BN - 1) / CfgDgelu::BN) * CfgDgelu::WAVES_N; }
 
@@ -686,15 +832,17 @@ static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
 template <int LAY>
 static moe_status launch_lay(GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
     switch (epi) {
-        case EPI_STORE: return launch_one<LAY, EPI_STORE, typename CfgFor<EPI_STORE>::type>(a, s);
-        case EPI_GELU: return launch_one<LAY, EPI_GELU, typename CfgFor<EPI_GELU>::type>(a, s);
-        case EPI_DGELU: return launch_one<LAY, EPI_DGELU, typename CfgFor<EPI_DGELU>::type>(a, s);
-        case EPI_ACCUM_F32: return launch_one<LAY, EPI_ACCUM_F32, typename CfgFor<EPI_ACCUM_F32>::type>(a, s);
-        case EPI_STORE_F32: return launch_one<LAY, EPI_STORE_F32, typename CfgFor<EPI_STORE_F32>::type>(a, s);
+        case EPI_STORE: return launch_one<LAY, EPI_STORE, typename CfgFor<LAY, EPI_STORE>::type>(a, s);
+        case EPI_GELU: return launch_one<LAY, EPI_GELU, typename CfgFor<LAY, EPI_GELU>::type>(a, s);
+        case EPI_DGELU: return launch_one<LAY, EPI_DGELU, typename CfgFor<LAY, EPI_DGELU>::type>(a, s);
+        case EPI_ACCUM_F32: return launch_one<LAY, EPI_ACCUM_F32, typename CfgFor<LAY, EPI_ACCUM_F32>::type>(a, s);
+        case EPI_STORE_F32: return launch_one<LAY, EPI_STORE_F32, typename CfgFor<LAY, EPI_STORE_F32>::type>(a, s);
     }
     return MOE_ERR_UNSUPPORTED;
 }
 
+}  // namespace moe
+namespace moe {
 moe_status gemm_bf16(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
     if (a.dw_part && a.dw_parts != gemm_bf16_dw_parts(a.N)) return MOE_ERR_SHAPE;
     // operand rows must be 16-byte aligned in memory
