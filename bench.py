@@ -59,7 +59,7 @@ def recorded_traffic(workload, n, reuse):
     return None
 
 
-def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0):
+def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0, group=0):
     """Time `steps` whole layer steps of one workload; returns the result dict and the inputs."""
     import numpy as np
     import torch
@@ -70,7 +70,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0):
     inp = synth.make_inputs(shape, seed=0)
     st = runner.LayerState(shape.T, shape.M, shape.H, shape.E, shape.k, shape.capacity_factor, n,
                            shape.dtype, reuse, second_stream=not args.single_stream,
-                           grad_overwrite=0 if args.accumulate else 1, fuse_gather=fuse)
+                           grad_overwrite=0 if args.accumulate else 1, fuse_gather=fuse, wgrad_group=group)
     st.upload(inp)
     st.zero_grads()
     torch.cuda.reset_peak_memory_stats()
@@ -110,6 +110,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0):
     ev_ms = ev0.elapsed_time(ev1)
     ms_per_step = wall_ms / steps
     peak_alloc = torch.cuda.max_memory_allocated()
+    ws_bytes = int(st.ws_total)
 
     counts = st.counts.cpu().numpy()
     slot = st.slot.cpu().numpy()
@@ -232,6 +233,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0):
         if mode >= 3:
             mem[f"mode{mode}"]["pinned_host"] = B.moe_offload_bytes(cfg)
     mem["max_memory_allocated_this_run"] = int(peak_alloc)
+    mem["this_run_workspace"] = ws_bytes
 
     out = {
         "metric": "MoE layer fwd+bwd tokens/sec", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
@@ -241,7 +243,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0):
         "data": "synthetic",
         "config": {"workload": f"{shape.name}: T={T} M={M} H={H} E={shape.E} k={k} cf={shape.capacity_factor}",
                    "n_partitions": n, "reuse_mode": reuse, "streams": 1 if args.single_stream else 2,
-                   "hip_graph": bool(args.graph), "fuse_gather": int(fuse),
+                   "hip_graph": bool(args.graph), "fuse_gather": int(fuse), "wgrad_group": int(group),
                    "weight_grads": "accumulated into zeroed buffers" if args.accumulate else "overwritten each step",
                    "kept_rows": R, "drop_rate": drop_rate},
         "tflops_model": flop_model / (ms_per_step * 1e-3) / 1e12,
@@ -260,13 +262,65 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0):
     }
     if brief:
         out = {"workload": out["config"]["workload"], "n_partitions": n, "reuse_mode": reuse, "fuse_gather": int(fuse),
-               "tokens_per_s": out["value"],
+               "wgrad_group": int(group), "tokens_per_s": out["value"],
                "ms_per_step": out["ms_per_step"], "tflops_executed": out["tflops_executed"],
                "gemm_tflops": roofline["achieved"], "gemm_frac_of_peak": roofline["frac"],
-               "drop_rate": drop_rate, "workspace_bytes": mem[f"mode{reuse}"]["workspace"]}
+               "drop_rate": drop_rate, "workspace_bytes": ws_bytes}
     del st
     torch.cuda.empty_cache()
     return out, shape, inp
+
+
+def memory_report(args, shape, inp):
+    """Peak device memory of one step per memory mode and partition count, measured (torch's allocator:
+    the library itself allocates nothing, so this is inputs + outputs + the workspace the mode asks for)
+    beside the analytic workspace and the paper's closed form for the saving (Section III-D, Eq. 5 with
+    kept rows in place of tokens: activations of one pass shrink by R (2M (n-2)/n + H (n-1)/n) elements,
+    and Eq. 4's temporaries by the same again)."""
+    import torch
+    from paper_2506_22175_amd import runner
+    es = 2 if shape.dtype == "bf16" else 4
+    rows = []
+    ns = [n for n in (1, 2, 4, 8) if shape.T % n == 0]
+    for n in ns:
+        base_peak = None
+        for mode, group in ((0, 0), (1, 0), (2, 0), (2, n)):
+            if group and n < 4:
+                continue
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+            before = torch.cuda.memory_allocated()
+            torch.cuda.reset_peak_memory_stats()
+            st = runner.LayerState(shape.T, shape.M, shape.H, shape.E, shape.k, shape.capacity_factor, n, shape.dtype,
+                                   mode, second_stream=not args.single_stream, grad_overwrite=1, wgrad_group=group)
+            st.upload(inp)
+            st.step()
+            torch.cuda.synchronize()
+            peak = torch.cuda.max_memory_allocated() - before
+            R = n * st.C_p * shape.E                                  # rows of all partition buffers
+            row = {"n_partitions": n, "reuse_mode": mode, "wgrad_group": group,
+                   "workspace_bytes": int(st.ws_total), "saved_activation_bytes": int(st.ws_saved),
+                   "temporary_bytes": int(st.ws_temp), "measured_peak_bytes": int(peak)}
+            if mode == 0 and not group:
+                base_peak, base_saved = peak, st.ws_saved
+            elif base_peak is not None and not group:
+                # Eq. 5: what sharing T_DI / T_DO (two buffers each) and, with recomputation, T_M (one buffer) saves
+                eq5 = R * (2 * shape.M * max(n - 2, 0) / n + (shape.H * (n - 1) / n if mode == 2 else 0.0)) * es
+                row["eq5_saving_bytes"] = int(eq5)
+                row["measured_saving_bytes"] = int(base_peak - peak)
+                row["saved_activation_saving_bytes"] = int(base_saved - st.ws_saved)
+                row["achieved_over_theoretical"] = (base_peak - peak) / eq5 if eq5 > 0 else None
+            elif base_peak is not None:
+                row["measured_saving_bytes"] = int(base_peak - peak)
+            rows.append(row)
+            del st
+    torch.cuda.empty_cache()
+    return {"per_mode_and_partitioning": rows,
+            "note": "measured_peak = torch.cuda.max_memory_allocated over one step, minus what was allocated before "
+                    "(x, dy, y, dx, weights, float weight gradients, routing outputs and the workspace). "
+                    "eq5_saving is the paper's forward-activation saving; the workspace also shares backward's "
+                    "temporaries, which is why achieved_over_theoretical can exceed 1 (the paper reports about "
+                    "95 % of its own model, Section V-C)"}
 
 
 def granularity_report(args, shape, inp, reuse):
@@ -312,6 +366,8 @@ def main():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--n", type=int, default=2, help="pipeline partitions")
     ap.add_argument("--reuse", type=int, default=2, help="0 keep all, 1 share buffers, 2 share + recompute")
+    ap.add_argument("--wgrad-group", type=int, default=0,
+                    help="partitions whose weight gradients are taken in one GEMM (0 or 1: every partition its own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--single-stream", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=16384, help="tokens of the workload the CPU oracle is timed on")
@@ -328,16 +384,18 @@ def main():
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
     out, shape, inp = measure(args, args.workload, args.n, args.reuse, args.steps, args.warmup,
-                              fuse=1 if args.fuse_gather else 0)
+                              fuse=1 if args.fuse_gather else 0, group=args.wgrad_group)
     if not args.no_sweep:
         # the other workloads of the set, a few steps each, for the record
         others = []
-        for wl, n, mode in (("small", 1, 2), ("gpt", 1, 2), ("gpt", 4, 2), ("skewed", 4, 2), ("large", 4, 2),
-                            ("large", 8, 2), (args.workload, args.n, 0), (args.workload, args.n, 1),
-                            (args.workload, args.n, 3), (args.workload, args.n, 4), (args.workload, args.n, 5)):
-            if wl == args.workload and n == args.n and mode == args.reuse:
+        for wl, n, mode, grp in (("small", 1, 2, 0), ("gpt", 1, 2, 0), ("gpt", 4, 2, 0), ("gpt", 4, 2, 2),
+                                 ("skewed", 4, 2, 0), ("skewed", 4, 2, 2), ("large", 4, 2, 0), ("large", 4, 2, 2),
+                                 ("large", 8, 2, 0), ("large", 8, 2, 4),
+                                 (args.workload, args.n, 0, 0), (args.workload, args.n, 1, 0),
+                                 (args.workload, args.n, 3, 0), (args.workload, args.n, 4, 0), (args.workload, args.n, 5, 0)):
+            if wl == args.workload and n == args.n and mode == args.reuse and grp == args.wgrad_group:
                 continue
-            o, _, _ = measure(args, wl, n, mode, 5, 2, brief=True)
+            o, _, _ = measure(args, wl, n, mode, 5, 2, brief=True, group=grp)
             others.append(o)
         # the same configuration with the other setting of the gathered first GEMM
         o, _, _ = measure(args, args.workload, args.n, args.reuse, 10, 3, brief=True, fuse=0 if args.fuse_gather else 1)
@@ -347,12 +405,14 @@ def main():
         names = {0: "none", 2: "S4", 3: "S1", 4: "S2", 5: "S3"}
         eq10 = out.get("interference_and_cost_model", {}).get("eq10", {})
         meas = {names[o["reuse_mode"]]: o["ms_per_step"] for o in others
-                if o["workload"] == out["config"]["workload"] and o["n_partitions"] == args.n and o["reuse_mode"] in names}
+                if o["workload"] == out["config"]["workload"] and o["n_partitions"] == args.n and o["reuse_mode"] in names
+                and o["wgrad_group"] == 0}
         meas[names.get(args.reuse, "mode 1")] = out["ms_per_step"]
         if eq10:
             out["interference_and_cost_model"]["measured_vs_eq10_step_ms"] = {
                 k_: {"measured": meas.get(k_), "eq10": v["step_ms"]} for k_, v in eq10.items()}
     if not args.no_sweep:
+        out["memory_bytes"]["measured"] = memory_report(args, shape, inp)
         out["adaptive_granularity"] = granularity_report(args, shape, inp, args.reuse)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, inp, args.cpu_tokens)

@@ -93,6 +93,13 @@ typedef struct {
                                into two partition-sized T_DI buffers for the weight-gradient
                                GEMM, as the shared-buffer modes do.  Not with S1 and S3, which
                                copy forward's T_DI to the host. */
+    int32_t wgrad_group;    /* 0 or 1: backward runs the two weight-gradient GEMMs once per partition
+                               (Table II's schedule).  G in 2..8: once per G consecutive partitions,
+                               reducing over all their rows in one GEMM, so the float gradients are
+                               read and written n/G times per step instead of n times; the price is
+                               G partition-sized buffers each of T_DI, dT_DO, T_M and dT_M alive in
+                               backward instead of two (one for T_M, dT_M).  Values above n count as
+                               n.  Not with S1..S3. */
 } moe_config;
 
 /* Host only.  C_p = ceil(capacity_factor * k * (T / n) / E), evaluated in double

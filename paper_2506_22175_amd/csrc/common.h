@@ -147,6 +147,7 @@ struct Dims {
     int overwrite;   // weight gradients are overwritten (first partition stores) instead of accumulated
     int renorm;      // combine weights are renormalised over the token's k choices
     int fuse;        // forward's first GEMM gathers its rows from the token-major input
+    int G;           // partitions per weight-gradient GEMM in backward (>= 1)
     size_t es;   // element size in bytes
 };
 
@@ -207,6 +208,11 @@ struct GemmArgs {
     int E, Cp;            // experts, max rows per expert
     int Mo;               // TN only: output rows
     int N, K;             // K unused for TN (K = counts[e])
+    // TN only: reduce over the rows of k_segs partitions in one launch (0 or 1: one).  Partition sg of
+    // the group has its counts at counts[sg*E + e] and its operands a_sstride / b_sstride elements
+    // after those of the partition before.  bf16 GEMM, at most 8.
+    int k_segs;
+    long long a_sstride, b_sstride;
     // epilogue operands
     void* Z;              // EPI_GELU: optional pre-activation out; EPI_DGELU: in/out
     int ldz;              // row stride of Z (elements); expert stride is Cp*ldz
@@ -235,5 +241,13 @@ moe_status ffn_fwd(const Dims& d, int part, const void* DI, const int* rows, con
 moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void* Z, const void* dDO,
                    const int* counts, const float* slot_w, const void* W1, const void* W2,
                    void* dZ, void* dDI, float* dW1, float* dW2, float* dw_part, hipStream_t s);
+// its two halves: everything but the weight gradients of one partition, and the weight gradients of
+// nparts consecutive partitions at once
+moe_status ffn_bwd_main(const Dims& d, int part, int recompute, const void* DI, void* Z, const void* dDO,
+                        const int* counts, const float* slot_w, const void* W1, const void* W2,
+                        void* dZ, void* dDI, float* dw_part, hipStream_t s);
+moe_status ffn_wgrad(const Dims& d, int part, int nparts, int store, const void* DI, const void* A, const void* dDO,
+                     const void* dZ, long long strideM, long long strideH, const int* counts,
+                     float* dW1, float* dW2, hipStream_t s);
 
 }  // namespace moe

@@ -30,6 +30,9 @@ moe_status make_dims(const moe_config* cfg, Dims* d) {
     if (cfg->fuse_gather != 0 && cfg->fuse_gather != 1) return MOE_ERR_UNSUPPORTED;
     if (cfg->fuse_gather && (cfg->reuse == MOE_REUSE_S1 || cfg->reuse == MOE_REUSE_S3)) return MOE_ERR_UNSUPPORTED;
     d->fuse = cfg->fuse_gather;
+    if (cfg->wgrad_group < 0 || cfg->wgrad_group > 8) return MOE_ERR_UNSUPPORTED;
+    d->G = cfg->wgrad_group < 1 ? 1 : (cfg->wgrad_group > d->n ? d->n : cfg->wgrad_group);
+    if (d->G > 1 && cfg->reuse > MOE_REUSE_RECOMPUTE) return MOE_ERR_UNSUPPORTED;   // not with the offloading strategies
     d->es = cfg->dtype == MOE_F32 ? 4 : 2;
     return MOE_OK;
 }

@@ -39,9 +39,9 @@ moe_status ffn_fwd(const Dims& d, int part, const void* DI, const int* rows, con
     return run_gemm(d, GEMM_NN, EPI_STORE, b, s);
 }
 
-moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void* Z, const void* dDO,
-                   const int* counts, const float* slot_w, const void* W1, const void* W2,
-                   void* dZ, void* dDI, float* dW1, float* dW2, float* dw_part, hipStream_t s) {
+moe_status ffn_bwd_main(const Dims& d, int part, int recompute, const void* DI, void* Z, const void* dDO,
+                        const int* counts, const float* slot_w, const void* W1, const void* W2,
+                        void* dZ, void* dDI, float* dw_part, hipStream_t s) {
     const int* cp = counts + (size_t)part * d.E;
     const long long eM = (long long)d.Cp * d.M, eH = (long long)d.Cp * d.H, wMH = (long long)d.M * d.H;
     if (recompute) {
@@ -65,14 +65,6 @@ moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void*
         a.dw_parts = d.dtype == MOE_F32 ? gemm_f32_dw_parts(d.H) : gemm_bf16_dw_parts(d.H);
         MOE_TRY(run_gemm(d, GEMM_NT, EPI_DGELU, a, s));
     }
-    {   // dW2[e] += (w gelu(Z))^T dDO
-        GemmArgs a = base_args(d, cp);
-        a.A = Z; a.lda = d.H; a.a_estride = eH; a.Mo = d.H;
-        a.B = dDO; a.ldb = d.M; a.b_estride = eM;
-        a.C = dW2; a.ldc = d.M; a.c_estride = wMH;
-        a.N = d.M;
-        MOE_TRY(run_gemm(d, GEMM_TN, (d.overwrite && part == 0) ? EPI_STORE_F32 : EPI_ACCUM_F32, a, s));
-    }
     {   // dDI = dZ W1^T
         GemmArgs a = base_args(d, cp);
         a.A = dZ; a.lda = d.H; a.a_estride = eH;
@@ -81,15 +73,50 @@ moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void*
         a.N = d.M; a.K = d.H;
         MOE_TRY(run_gemm(d, GEMM_NT, EPI_STORE, a, s));
     }
-    {   // dW1[e] += DI^T dZ
-        GemmArgs a = base_args(d, cp);
-        a.A = DI; a.lda = d.M; a.a_estride = eM; a.Mo = d.M;
-        a.B = dZ; a.ldb = d.H; a.b_estride = eH;
-        a.C = dW1; a.ldc = d.H; a.c_estride = wMH;
-        a.N = d.H;
-        MOE_TRY(run_gemm(d, GEMM_TN, (d.overwrite && part == 0) ? EPI_STORE_F32 : EPI_ACCUM_F32, a, s));
+    return MOE_OK;
+}
+
+// Both weight gradients over the rows of `nparts` consecutive partitions starting at `part`, whose
+// buffers lie strideM (T_DI, dT_DO) and strideH (weighted activations, dT_M) elements apart.  The
+// reduction over a partition's rows and the sum over partitions are one GEMM, so the float gradients
+// are read and written once per group instead of once per partition.
+moe_status ffn_wgrad(const Dims& d, int part, int nparts, int store, const void* DI, const void* A, const void* dDO,
+                     const void* dZ, long long strideM, long long strideH, const int* counts,
+                     float* dW1, float* dW2, hipStream_t s) {
+    const long long eM = (long long)d.Cp * d.M, eH = (long long)d.Cp * d.H, wMH = (long long)d.M * d.H;
+    // the float GEMM reduces one partition per launch
+    const int per_launch = d.dtype == MOE_F32 ? 1 : nparts;
+    for (int q = 0; q < nparts; q += per_launch) {
+        const int* cp = counts + (size_t)(part + q) * d.E;
+        const GemmEpilogue epi = (store && q == 0) ? EPI_STORE_F32 : EPI_ACCUM_F32;
+        const size_t oM = (size_t)q * strideM * d.es, oH = (size_t)q * strideH * d.es;
+        {   // dW2[e] += (w gelu(Z))^T dDO
+            GemmArgs a = base_args(d, cp);
+            a.A = (const char*)A + oH; a.lda = d.H; a.a_estride = eH; a.Mo = d.H;
+            a.B = (const char*)dDO + oM; a.ldb = d.M; a.b_estride = eM;
+            a.C = dW2; a.ldc = d.M; a.c_estride = wMH;
+            a.N = d.M;
+            a.k_segs = per_launch; a.a_sstride = strideH; a.b_sstride = strideM;
+            MOE_TRY(run_gemm(d, GEMM_TN, epi, a, s));
+        }
+        {   // dW1[e] += DI^T dZ
+            GemmArgs a = base_args(d, cp);
+            a.A = (const char*)DI + oM; a.lda = d.M; a.a_estride = eM; a.Mo = d.M;
+            a.B = (const char*)dZ + oH; a.ldb = d.H; a.b_estride = eH;
+            a.C = dW1; a.ldc = d.H; a.c_estride = wMH;
+            a.N = d.H;
+            a.k_segs = per_launch; a.a_sstride = strideM; a.b_sstride = strideH;
+            MOE_TRY(run_gemm(d, GEMM_TN, epi, a, s));
+        }
     }
     return MOE_OK;
+}
+
+moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void* Z, const void* dDO,
+                   const int* counts, const float* slot_w, const void* W1, const void* W2,
+                   void* dZ, void* dDI, float* dW1, float* dW2, float* dw_part, hipStream_t s) {
+    MOE_TRY(ffn_bwd_main(d, part, recompute, DI, Z, dDO, counts, slot_w, W1, W2, dZ, dDI, dw_part, s));
+    return ffn_wgrad(d, part, 1, d.overwrite && part == 0, DI, Z, dDO, dZ, 0, 0, counts, dW1, dW2, s);
 }
 
 }  // namespace moe

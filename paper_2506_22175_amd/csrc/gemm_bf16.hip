@@ -182,11 +182,15 @@ struct NCTile {
     v4i rsrc;
     unsigned voff[NI];
     unsigned kstep;          // bytes per k row in memory
+    // descriptor of rows [0, K) x columns [0, n_valid) of the matrix at P
+    static __device__ __forceinline__ v4i rsrc_of(const bf16_t* P, int ld, int n_valid, int K) {
+        return make_rsrc(P, K > 0 ? (unsigned)(((size_t)(K - 1) * ld + n_valid) * 2) : 0u);
+    }
     // P: operand base of this expert ([k][n], n contiguous); rows [0, K) x columns [n0, n_limit) valid
     __device__ __forceinline__ void init(const bf16_t* P, int ld, int n0, int n_limit, int K, int lane, int wid) {
         const int n_valid = n_limit - n0;
-        rsrc = make_rsrc(P + n0, K > 0 ? (unsigned)(((size_t)(K - 1) * ld + n_valid) * 2) : 0u);
         kstep = (unsigned)ld * 2u;
+        rsrc = rsrc_of(P + n0, ld, n_valid, K);
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int q = wid * NI + j;
@@ -263,7 +267,12 @@ __device__ __forceinline__ void mfma_pinned(floatx16& acc, const bf16x8& a, cons
         asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b) : "memory");
 }
 
+// TN only: the reduction dimension may run over the rows of several partitions (up to MAX_KSEGS row
+// ranges, one per partition buffer); tiles of 32 k never straddle two ranges.  KCursor says which range
+// the tile that is being requested lies in and where.
+constexpr int MAX_KSEGS = 8;
 struct TileCoord { int e, tn, m0, n0, Mdim, Kdim, KT; };
+struct KCursor { int seg, jl, tiles; };
 
 // Persistent workgroups: the grid has one workgroup per CU, and workgroup b works through
 // the tiles b, b + grid, b + 2 grid, ...  While a tile's epilogue runs (it needs only the
@@ -336,6 +345,16 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
         t.m0 = tm * BM;
         t.n0 = t.tn * BN;
         t.KT = (t.Kdim + BK - 1) / BK;
+        if constexpr (LAY == GEMM_TN) {
+            if (g.k_segs > 1) {
+                t.Kdim = 0; t.KT = 0;
+                for (int sg = 0; sg < g.k_segs; ++sg) {
+                    const int r = g.counts[sg * g.E + e];
+                    t.Kdim += r;
+                    t.KT += (r + BK - 1) / BK;
+                }
+            }
+        }
         if (t.m0 >= t.Mdim) return false;
         if (t.Kdim <= 0 && EPI != EPI_STORE_F32) return false;   // nothing to add; a plain store still writes zeros
         return true;
@@ -359,7 +378,30 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
         if (!gathered) ta_.init(A, g.lda, t.m0, t.Mdim, t.Kdim, lane, wid);
         tb_.init(B, g.ldb, t.n0, g.N, t.Kdim, lane, wid);
     };
-    auto request = [&](const AT& ta_, const BT& tb_, char* st, int k0, int l) {   // load l of the tile starting at k0
+    // load l of the tile that starts at k0.  Over several row ranges (TN) the tiles are requested in
+    // ascending order, each starting with its load 0: that is where the cursor moves on, into the next
+    // range with rows where the last one is used up (its operands then get new descriptors), and past
+    // the last range, where everything reads as zeros.
+    auto request = [&](const TileCoord& tc, KCursor& kc_, AT& ta_, BT& tb_, char* st, int k0, int l) {
+        if constexpr (LAY == GEMM_TN) {
+            if (g.k_segs > 1) {
+                if (l == 0) {
+                    if (k0 == 0) { kc_.seg = -1; kc_.jl = 0; kc_.tiles = 0; } else ++kc_.jl;
+                    while (kc_.jl >= kc_.tiles) {
+                        ++kc_.seg;
+                        kc_.jl = 0;
+                        const bool more = kc_.seg < g.k_segs;
+                        const int rows = more ? g.counts[kc_.seg * g.E + tc.e] : 0;
+                        kc_.tiles = more ? (rows + BK - 1) / BK : 0x7fffffff;
+                        const bf16_t* A = (const bf16_t*)g.A + (size_t)tc.e * g.a_estride + kc_.seg * g.a_sstride + tc.m0;
+                        const bf16_t* B = (const bf16_t*)g.B + (size_t)tc.e * g.b_estride + kc_.seg * g.b_sstride + tc.n0;
+                        ta_.rsrc = AT::rsrc_of(A, g.lda, tc.Mdim - tc.m0, rows);
+                        tb_.rsrc = BT::rsrc_of(B, g.ldb, g.N - tc.n0, rows);
+                    }
+                }
+                k0 = kc_.jl * BK;
+            }
+        }
         if (l < AT::NI) ta_.load_one(st, k0, wid, l);
         else tb_.load_one(st + A_BYTES, k0, wid, l - AT::NI);
     };
@@ -376,7 +418,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     constexpr int NL = W64 ? (A_WIDE ? BT::NI : AT::NI) : 0;       //                 one narrow tile (4)
     static_assert(!W64 || (WL == 8 && NL == 4), "the two-ring schedule issues two wide and two narrow loads per block");
     // the part of a tile's first loads that does not touch the staging region, and the rest
-    auto issue_early = [&](const AT& ta_, const BT& tb_) {
+    auto issue_early = [&](const TileCoord& tc, KCursor& kc_, AT& ta_, BT& tb_) {
         if constexpr (W64) {
             // what the loop expects to be on its way when it starts: wide units 0 and 1 and the first
             // quarter of unit 2 (late: its slot is the staging region), narrow tiles 0..2 and half of tile 3
@@ -396,21 +438,21 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
 #pragma unroll
             for (int s = 0; s < 3; ++s)
 #pragma unroll
-                for (int l = 0; l < LPW; ++l) request(ta_, tb_, smem + (SB + s) * STAGE, s * BK, l);
+                for (int l = 0; l < LPW; ++l) request(tc, kc_, ta_, tb_, smem + (SB + s) * STAGE, s * BK, l);
         } else {
             ta_.load(smem + SB * STAGE, 0, wid);
             tb_.load(smem + SB * STAGE + A_BYTES, 0, wid);
         }
     };
-    auto issue_late = [&](const AT& ta_, const BT& tb_) {
+    auto issue_late = [&](const TileCoord& tc, KCursor& kc_, AT& ta_, BT& tb_) {
         if constexpr (W64) {
 #pragma unroll
             for (int l = 0; l < WL / 4; ++l) load_wide(ta_, tb_, 2, 2, l);
         } else if constexpr (C::PIPE) {
 #pragma unroll
-            for (int l = 0; l < LPW; ++l) request(ta_, tb_, smem, 3 * BK, l);
+            for (int l = 0; l < LPW; ++l) request(tc, kc_, ta_, tb_, smem, 3 * BK, l);
 #pragma unroll
-            for (int l = 0; l < LPW / 2; ++l) request(ta_, tb_, smem + STAGE, 4 * BK, l);
+            for (int l = 0; l < LPW / 2; ++l) request(tc, kc_, ta_, tb_, smem + STAGE, 4 * BK, l);
         }
     };
 
@@ -420,8 +462,9 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     AT ta;
     BT tb;
     bind(cur, ta, tb);
-    issue_early(ta, tb);
-    issue_late(ta, tb);
+    KCursor kc = {0, 0, 0};
+    issue_early(cur, kc, ta, tb);
+    issue_late(cur, kc, ta, tb);
     bool first = true;
 
     for (;;) {
@@ -554,7 +597,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                     mfma_pinned<C::OCC == 1>(acc[m / TNN][m % TNN], F0[TM + m % TNN], F0[m / TNN]);
                     if (m < TM) F1[m] = fa[m].read(cs, 1);
                     else if (m < FR) F1[m] = fb[m - TM].read(cs + A_BYTES, 1);
-                    else if (m - FR < LS * (LPW / 2) && (m - FR) % LS == 0) request(ta, tb, prv, (kt + 4) * BK, LPW / 2 + (m - FR) / LS);
+                    else if (m - FR < LS * (LPW / 2) && (m - FR) % LS == 0) request(cur, kc, ta, tb, prv, (kt + 4) * BK, LPW / 2 + (m - FR) / LS);
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave no longer reads stage t
                 wait_vmcnt<3 * LPW>();                               // its part of tile t+1 is in
@@ -565,7 +608,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                     mfma_pinned<C::OCC == 1>(acc[m / TNN][m % TNN], F1[TM + m % TNN], F1[m / TNN]);
                     if (m < TM) F0[m] = fa[m].read(nxt, 0);
                     else if (m < FR) F0[m] = fb[m - TM].read(nxt + A_BYTES, 0);
-                    else if (m - FR < LS * (LPW / 2) && (m - FR) % LS == 0) request(ta, tb, cs, (kt + 5) * BK, (m - FR) / LS);
+                    else if (m - FR < LS * (LPW / 2) && (m - FR) % LS == 0) request(cur, kc, ta, tb, cs, (kt + 5) * BK, (m - FR) / LS);
                 }
                 st = stn;
             }
@@ -611,6 +654,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
         TileCoord nx;
         AT ta2;
         BT tb2;
+        KCursor kc2 = {0, 0, 0};
         const int vn = next_tile(vb + (int)gridDim.x, nx);
         if (vn >= 0) bind(nx, ta2, tb2);
 
@@ -687,18 +731,24 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
             if constexpr (READS) { if (ps + 1 < NPASS) request_pass(ps + 1, pin[(ps + 1) & 1]); }
             const PassIn& in = pin[ps & 1];
             // all LDS reads of the pass before its arithmetic: one round trip through LDS, not one per piece
+            // (float accumulation keeps the old sums of two passes in registers and has none left for that)
+            constexpr bool HOIST = EPI != EPI_ACCUM_F32;
             float4 lo[NPIECE], hi[NPIECE];
-#pragma unroll
-            for (int t = 0; t < NPIECE; ++t) {
+            auto read_piece = [&](int t) {
                 const int idx = lane + 64 * t;
                 const int row = idx / CPRW, c8 = idx % CPRW;
                 lo[t] = *reinterpret_cast<const float4*>(stage + row * CW + (((2 * c8) ^ (row & 15)) << 2));
                 hi[t] = *reinterpret_cast<const float4*>(stage + row * CW + (((2 * c8 + 1) ^ (row & 15)) << 2));
+            };
+            if constexpr (HOIST) {
+#pragma unroll
+                for (int t = 0; t < NPIECE; ++t) read_piece(t);
             }
 #pragma unroll
             for (int t = 0; t < NPIECE; ++t) {
                 int m, c8, row; unsigned oC, oZ;
                 piece(ps, t, m, c8, row, oC, oZ);
+                if constexpr (!HOIST) read_piece(t);
                 float v[8] = {lo[t].x, lo[t].y, lo[t].z, lo[t].w, hi[t].x, hi[t].y, hi[t].z, hi[t].w};
                 if constexpr (EPI == EPI_STORE) {
                     uint4 o = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
@@ -751,7 +801,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
             }
             // the next tile's first operand tiles start their trip once the first pass is through
             // (earlier, and this pass's own reads would have to wait behind them)
-            if (ps == 0 && vn >= 0) issue_early(ta2, tb2);
+            if (ps == 0 && vn >= 0) issue_early(nx, kc2, ta2, tb2);
         }
         if (vn < 0) break;
         // Everything this wave has in flight is through: the next tile's first operand tiles have
@@ -761,7 +811,8 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();                // every wave is done with the staging stages
         asm volatile("" ::: "memory");
-        issue_late(ta2, tb2);
+        issue_late(nx, kc2, ta2, tb2);
+        kc = kc2;
         ta = ta2;
         tb = tb2;
         cur = nx;
@@ -851,6 +902,7 @@ moe_status gemm_bf16(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStr
     const long long ldmax = a.lda > a.ldb ? a.lda : a.ldb;
     const long long rmax = a.Cp > a.K ? a.Cp : a.K;
     if ((rmax + 8 * 64) * ldmax * 2 >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
+    if (a.k_segs > 1 && (lay != GEMM_TN || a.k_segs > MAX_KSEGS)) return MOE_ERR_UNSUPPORTED;
     if (a.a_rows) {
         // gathered rows: only for the row operand of NN / NT, and the whole matrix must stay below 2 GiB
         if (lay == GEMM_TN || a.a_row_limit <= 0) return MOE_ERR_UNSUPPORTED;

@@ -23,10 +23,10 @@ static inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 struct Workspace {
     // M-wide partition buffers
     size_t DI, DO, dDO, dDI;          // offsets; each region holds nDI / nDO / 2 / 2 buffers
-    int nDI, nDO;
+    int nDI, nDO, ndDO;
     bool dDO_aliases_DO;
     // H-wide
-    size_t Z, HT;                     // Z: nZ buffers; HT: one temporary (forward A, backward dZ)
+    size_t Z, HT;                     // Z: nZ buffers; HT: G temporaries (forward A in the first, backward dZ)
     int nZ;
     // routing-class data
     size_t slot_w, dw, dw_part, dL, gate_scratch, slot_scratch, rows;
@@ -51,10 +51,14 @@ static moe_status plan(const moe_config* cfg, const Dims& d, Workspace* w) {
     w->bufM = align_up((size_t)d.Rp * d.M * d.es);
     w->bufH = align_up((size_t)d.Rp * d.H * d.es);
     const bool reuse = d.reuse != MOE_REUSE_NONE;
-    // with the gathered first GEMM forward keeps no T_DI at all; backward dispatches into two buffers
-    w->nDI = ((reuse || d.fuse) && d.n > 2) ? 2 : d.n;
-    w->nDO = (reuse && d.n > 2) ? 2 : d.n;
-    w->nZ = mode_recomputes(d.reuse) ? 1 : mode_offloads_z(d.reuse) ? (d.n < 2 ? d.n : 2) : d.n;
+    // Partition buffers of T_DI and dT_DO that backward keeps alive: two (one being filled while the other
+    // is read), or the G partitions whose weight gradients are taken in one GEMM.
+    const int alive = d.G > 2 ? d.G : 2;
+    // with the gathered first GEMM forward keeps no T_DI at all; backward dispatches into `alive` buffers
+    w->nDI = ((reuse || d.fuse) && d.n > alive) ? alive : d.n;
+    w->nDO = (reuse && d.n > alive) ? alive : d.n;
+    w->nZ = mode_recomputes(d.reuse) ? d.G : mode_offloads_z(d.reuse) ? (d.n < 2 ? d.n : 2) : d.n;
+    w->ndDO = reuse ? w->nDO : (d.n > alive ? alive : d.n);
     w->dDO_aliases_DO = reuse;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
@@ -62,8 +66,8 @@ static moe_status plan(const moe_config* cfg, const Dims& d, Workspace* w) {
     w->DO = take(w->bufM * w->nDO);
     w->Z = take(w->bufH * w->nZ);
     w->saved = off;
-    w->HT = take(w->bufH);
-    w->dDO = reuse ? w->DO : take(w->bufM * 2);
+    w->HT = take(w->bufH * d.G);
+    w->dDO = reuse ? w->DO : take(w->bufM * w->ndDO);
     w->dDI = take(w->bufM * 2);
     w->temp = off - w->saved;
     const size_t r0 = off;
@@ -101,14 +105,14 @@ static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace&
                           void* y, float* logits, int* topk_idx, float* topk_w, int* slot, int* counts,
                           hipStream_t s0, hipStream_t s1, const Offload* off = nullptr) {
     const int n = d.n;
-    MOE_TRY(get_events(6 * (size_t)n + 2));
+    MOE_TRY(get_events(7 * (size_t)n + 2));
     hipEvent_t* evS = g_events.data();
     hipEvent_t* evC = evS + n;
     hipEvent_t* evR = evC + n;
     hipEvent_t* evDIout = evR + n;            // T_DI of p is on the host
     hipEvent_t* evZout = evDIout + n;         // T_M of p is on the host
-    hipEvent_t evFork = g_events[6 * (size_t)n];
-    hipEvent_t evCopies = g_events[6 * (size_t)n + 1];
+    hipEvent_t evFork = g_events[7 * (size_t)n];
+    hipEvent_t evCopies = g_events[7 * (size_t)n + 1];
     const bool off_di = off && mode_offloads_di(d.reuse), off_z = off && mode_offloads_z(d.reuse);
 
     MOE_TRY(moe_route(cfg, x, Wg, gate_bias, logits, topk_idx, topk_w, s0));
@@ -172,13 +176,14 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
                            void* dx, float* dWg, float* dW1, float* dW2,
                            const float* logits, const int* topk_idx, const int* slot, const int* counts,
                            hipStream_t s0, hipStream_t s1, const Offload* off = nullptr) {
-    const int n = d.n;
-    MOE_TRY(get_events(6 * (size_t)n + 2));
+    const int n = d.n, G = d.G;
+    MOE_TRY(get_events(7 * (size_t)n + 2));
     hipEvent_t* evS = g_events.data();        // R'_p done (rows of dy, and of x again, are in place)
-    hipEvent_t* evC = evS + n;                // backward GEMMs of p done
+    hipEvent_t* evC = evS + n;                // backward GEMMs of p done, weight gradients apart
     hipEvent_t* evD = evC + n;                // S'_p done (dDI and dw_part of p consumed)
     hipEvent_t* evIn = evD + n;               // T_DI / T_M of p are back from the host
-    hipEvent_t evFork = g_events[6 * (size_t)n];
+    hipEvent_t* evW = evIn + n;               // weight gradients of group g done
+    hipEvent_t evFork = g_events[7 * (size_t)n];
     const bool reuse = d.reuse != MOE_REUSE_NONE;
     const bool recompute = mode_recomputes(d.reuse);
     const bool off_di = off && mode_offloads_di(d.reuse), off_z = off && mode_offloads_z(d.reuse);
@@ -186,12 +191,15 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
     auto DIbuf = [&](int p) { return ws + w.DI + w.bufM * (p % w.nDI); };
     auto DObuf = [&](int p) { return ws + w.DO + w.bufM * (p % w.nDO); };
     auto Zbuf = [&](int p) { return ws + w.Z + w.bufH * (p % w.nZ); };
-    auto dDObuf = [&](int p) { return ws + w.dDO + w.bufM * (p % 2); };
+    auto dZbuf = [&](int p) { return ws + w.HT + w.bufH * (p % G); };
+    auto dDObuf = [&](int p) { return ws + w.dDO + w.bufM * (p % w.ndDO); };
     auto dDIbuf = [&](int p) { return ws + w.dDI + w.bufM * (p % 2); };
     auto dwpart = [&](int p) { return (float*)(ws + w.dw_part + w.dw_part_bytes * (p % 2)); };
     float* dw = (float*)(ws + w.dw);
     float* dL = (float*)(ws + w.dL);
     const float* slot_w = (const float*)(ws + w.slot_w);
+    // forward left T_DI of every partition in place unless buffers are shared or it never wrote any
+    const bool redispatch = !off_di && (w.nDI < n || d.fuse);
 
     HIP_TRY(hipEventRecord(evFork, s0));
     HIP_TRY(hipStreamWaitEvent(s1, evFork, 0));
@@ -200,14 +208,14 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
 
     for (int p = 0; p <= n; ++p) {
         if (p < n) {
-            // R'_p: rows of dy to the experts.  Their buffer (and the re-dispatched T_DI
-            // buffer) was last read by the GEMMs of partition p-2.
-            if (p >= 2) HIP_TRY(hipStreamWaitEvent(s0, evC[p - 2], 0));
+            // R'_p: rows of dy to the experts.  Their buffer (and the re-dispatched T_DI buffer) was last
+            // read by partition p - (number of buffers): by its GEMMs and by the weight-gradient GEMMs of
+            // its group, which come last.
+            if (p >= w.ndDO) HIP_TRY(hipStreamWaitEvent(s0, evW[(p - w.ndDO) / G], 0));
+            if (redispatch && p >= w.nDI && w.nDI != w.ndDO) HIP_TRY(hipStreamWaitEvent(s0, evW[(p - w.nDI) / G], 0));
             if (reuse) {
                 MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), nullptr, nullptr, s0));
-                // T_DI from T_I again - unless every partition still has its own buffer (n <= 2 shares
-                // nothing), which then holds what forward put there
-                if (!off_di && (w.nDI < n || d.fuse)) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
+                if (redispatch) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
             } else {
                 // T_DO was kept: the combine-weight gradient is <dy_t, T_DO row>
                 MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), DObuf(p), dw, s0));
@@ -217,7 +225,7 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
             if (off_di || off_z) {
                 // what was offloaded comes back into the shared buffers, last read by the GEMMs of p-2
                 // (the copy stream runs in order, so the forward copies are through)
-                if (p >= 2) HIP_TRY(hipStreamWaitEvent(off->s2, evC[p - 2], 0));
+                if (p >= 2) HIP_TRY(hipStreamWaitEvent(off->s2, evW[p - 2], 0));
                 if (off_di)
                     HIP_TRY(hipMemcpyAsync(DIbuf(p), off->host + off->DI + w.bufM * p, w.bufM, hipMemcpyHostToDevice, off->s2));
                 if (off_z)
@@ -225,12 +233,20 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
                 HIP_TRY(hipEventRecord(evIn[p], off->s2));
                 HIP_TRY(hipStreamWaitEvent(s1, evIn[p], 0));
             }
-            // C'_p
+            // C'_p: everything but the weight gradients
             HIP_TRY(hipStreamWaitEvent(s1, evS[p], 0));
             if (p >= 2) HIP_TRY(hipStreamWaitEvent(s1, evD[p - 2], 0));
-            MOE_TRY(ffn_bwd(d, p, recompute ? 1 : 0, DIbuf(p), Zbuf(p), dDObuf(p), counts, slot_w, W1, W2,
-                            ws + w.HT, dDIbuf(p), dW1, dW2, reuse ? dwpart(p) : nullptr, s1));
+            MOE_TRY(ffn_bwd_main(d, p, recompute ? 1 : 0, DIbuf(p), Zbuf(p), dDObuf(p), counts, slot_w, W1, W2,
+                                 dZbuf(p), dDIbuf(p), reuse ? dwpart(p) : nullptr, s1));
             HIP_TRY(hipEventRecord(evC[p], s1));
+            // the weight gradients of a whole group after its last partition (Section III-B's per-partition
+            // schedule when G = 1)
+            if (p % G == G - 1 || p == n - 1) {
+                const int p0 = p / G * G;
+                MOE_TRY(ffn_wgrad(d, p0, p - p0 + 1, d.overwrite && p0 == 0, DIbuf(p0), Zbuf(p0), dDObuf(p0), dZbuf(p0),
+                                  (long long)(w.bufM / d.es), (long long)(w.bufH / d.es), counts, dW1, dW2, s1));
+                HIP_TRY(hipEventRecord(evW[p / G], s1));
+            }
         }
         if (p >= 1) {
             // S'_{p-1}: gate backward and rows of dDI back to token order
@@ -242,6 +258,7 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
             HIP_TRY(hipEventRecord(evD[q], s0));
         }
     }
+    HIP_TRY(hipStreamWaitEvent(s0, evW[(n - 1) / G], 0));      // the last weight gradients belong to the step
     return MOE_OK;
 }
 

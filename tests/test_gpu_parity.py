@@ -439,6 +439,61 @@ def test_large_workload_sampled(oracle, runner):
 
 
 # ---------------------------------------------------------------------------------
+# weight gradients of several partitions in one GEMM (wgrad_group)
+# ---------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("case", ["small", "ragged_bf16", "heavy_drops_bf16", "skew_empty_experts_bf16", "ragged_f32",
+                                  "one_token_per_partition"])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_grouped_weight_gradients_full_parity(oracle, runner, case, mode):
+    """The reduction over the rows of G partitions as one GEMM (float32: G GEMMs in a row) gives the
+    oracle's gradients for every memory mode, with groups that do and do not divide n, experts without
+    rows in some partitions, and gradients stored by the first group or accumulated."""
+    if case == "small":
+        s, n = synth.WORKLOADS["small"], 4
+    else:
+        name, T, M, H, E, k, cf, dt, n, zipf = next(c for c in CASES if c[0] == case)
+        kw = dict(zipf_s=1.2, zipf_tau=zipf) if zipf else {}
+        s = synth.custom_shape(T, M, H, E, k, cf, dtype=dt, x_std=1.0, w_std=0.05, name=name, **kw)
+    d = synth.make_inputs(s, seed=3)
+    r = _oracle(oracle, s, d, n)
+    for G, overwrite in ((2, 0), (3, 1), (8, 0)):
+        g = runner.run_layer_step(s, d, n, mode, wgrad_group=G, grad_overwrite=overwrite)
+        _check_routing(g, r)
+        _check_values(g, r, TOL[s.dtype])
+
+
+@pytest.mark.parametrize("n,G", [(4, 2), (8, 4), (8, 8)])
+def test_large_workload_grouped_weight_gradients_full_oracle(oracle, runner, n, G):
+    s = synth.WORKLOADS["large"]
+    d, r = _oracle_once(oracle, "large", n)
+    g = runner.run_layer_step(s, d, n, 2, grad_overwrite=1, wgrad_group=G)
+    _check_routing(g, r)
+    _check_values(g, r, TOL["bf16"])
+
+
+def test_launch_counts_with_grouped_weight_gradients(runner):
+    """Per partition backward still runs Table II's GEMM units other than the two weight-gradient
+    ones (2, or 3 with recomputation); those two run once per group."""
+    from paper_2506_22175_amd import binding as B
+    s = synth.WORKLOADS["small"]
+    d = synth.make_inputs(s, seed=0)
+    n = 4
+    for mode, per_part in ((0, 2), (2, 3)):
+        for G, groups in ((1, 4), (2, 2), (3, 2), (4, 1)):
+            st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, n, s.dtype, mode, wgrad_group=G)
+            st.upload(d)
+            st.zero_grads()
+            st.forward()
+            torch.cuda.synchronize()
+            B.moe_launch_counts(reset=True)
+            st.backward()
+            torch.cuda.synchronize()
+            g, p, _ = B.moe_launch_counts(reset=True)
+            assert g == per_part * n + 2 * groups, (mode, G, g)
+
+
+# ---------------------------------------------------------------------------------
 # schedule: op counts of Table II, and the entry points one by one
 # ---------------------------------------------------------------------------------
 
