@@ -179,50 +179,6 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0, group=
                 gbs = nbytes * per_step * 3 / (ms * 1e-3) / 1e9
                 hbm_alone[name] = {"avg_us": 1e3 * ms / l, "GB/s": gbs, "frac": gbs / PEAK_HBM_GBS}
         others_alone = {kd: prof1[kd][1] / 3 for kd in ("route", "slots", "gate_bwd")}
-        # interference and the strategy cost model (Sections II-C, III-E): speeds alone, relative speeds
-        # when GEMMs and permutations run side by side, Eq. 10 per micro-batch against the measured step
-        g_alone_ms = sum(prof1[kd][1] for kd in GEMM_KINDS) / 3
-        perm_corun_ms = (prof["dispatch"][1] + prof["combine"][1]) / steps
-        perm_alone_ms = (prof1["dispatch"][1] + prof1["combine"][1]) / 3
-        if g_alone_ms > 0 and perm_alone_ms > 0 and perm_corun_ms > 0:
-            rows_pp = R / n                                              # kept rows of a micro-batch
-            exchanges = (n_disp_per_step + 1) * n                        # dispatch and combine launches per step
-            sp = B.MoESpeeds(W_comp=g_flop_per_step / 2.0 / (g_alone_ms * 1e-3),
-                             W_comm=exchanges * rows_pp * M / (perm_alone_ms * 1e-3), W_mem=1.0,
-                             sigma=min(1.0, g_alone_ms / (g_ms / steps)), mu_comp=min(1.0, perm_alone_ms / perm_corun_ms),
-                             mu_all=1.0, eta_all=1.0)
-            model = {}
-            for name, num in (("none", 0), ("S4", 4)):
-                fw, bw = B.moe_strategy_cost(num, int(round(rows_pp)), M, H, sp)
-                model[name] = {"fw_ms_per_microbatch": fw * 1e3, "bw_ms_per_microbatch": bw * 1e3,
-                               "step_ms": n * (fw + bw) * 1e3}
-            # host copies: elements of the storage type per second over PCIe, measured alone
-            hb = torch.empty((256 << 20,), dtype=torch.uint8, pin_memory=True)
-            db = torch.empty((256 << 20,), dtype=torch.uint8, device=st.device)
-            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            hb.copy_(db, non_blocking=True)
-            torch.cuda.synchronize()
-            c0.record()
-            hb.copy_(db, non_blocking=True)
-            db.copy_(hb, non_blocking=True)
-            c1.record()
-            torch.cuda.synchronize()
-            sp.W_mem = 2.0 * (256 << 20) / es / (c0.elapsed_time(c1) * 1e-3)
-            sp.mu_all = sp.mu_comp
-            del hb, db
-            for name, num in (("S1", 1), ("S2", 2), ("S3", 3)):
-                fw, bw = B.moe_strategy_cost(num, int(round(rows_pp)), M, H, sp)
-                model[name] = {"fw_ms_per_microbatch": fw * 1e3, "bw_ms_per_microbatch": bw * 1e3,
-                               "step_ms": n * (fw + bw) * 1e3}
-            pick, _ = B.moe_select_strategy(0b10001, int(round(rows_pp)), M, H, sp)
-            pick_all, _ = B.moe_select_strategy(0b11110, int(round(rows_pp)), M, H, sp)
-            cost_model = {"W_comp_TMAC_per_s": sp.W_comp / 1e12, "W_comm_Gelem_per_s": sp.W_comm / 1e9,
-                          "sigma_comp_beside_permutations": sp.sigma, "mu_permutations_beside_comp": sp.mu_comp,
-                          "W_mem_Gelem_per_s": sp.W_mem / 1e9,
-                          "eq10": model, "cheapest_of_none_and_S4": B.STRATEGIES[pick],
-                          "cheapest_memory_saving_strategy": B.STRATEGIES[pick_all],
-                          "this_run": {"strategy": {0: "none", 2: "S4"}.get(reuse, "mode 1 (no row in Table II)"),
-                                       "measured_step_ms": ms_per_step}}
 
     mem = {}
     for mode in (0, 1, 2, 3, 4, 5):
@@ -257,6 +213,7 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0, group=
         "other_kernels_ms_per_step": {kd: prof[kd][1] / steps for kd in ("route", "slots", "gate_bwd")},
         "other_kernels_alone_ms_per_step": others_alone,
         "interference_and_cost_model": cost_model,
+        "_kept_rows": R,
         "paper_context": "MPipeMoE reports up to 2.8x speedup and up to 47% less memory than FasterMoE on 64 A100 "
                          "GPUs (8 DGX A100); ratios on other hardware, not a target for this number",
     }
@@ -385,6 +342,23 @@ def main():
 
     out, shape, inp = measure(args, args.workload, args.n, args.reuse, args.steps, args.warmup,
                               fuse=1 if args.fuse_gather else 0, group=args.wgrad_group)
+    kept_rows = out.pop("_kept_rows")
+    if not args.no_sweep:
+        # Section II-C's slowdown factors as real co-runs, and Eq. 10 with them (Section III-E)
+        from paper_2506_22175_amd import measure as msr
+        itf = msr.interference(shape, inp, args.n, args.reuse, wgrad_group=args.wgrad_group)
+        units = args.n * (2 + 4 + (1 if args.reuse in (2, 5) else 0))
+        co_r = min((r for r in itf["side_by_side"] if r["free_cus"] > 0), key=lambda r: r["step_ms"])["free_cus"]
+        model = msr.strategy_model(shape, args.n, kept_rows, units, itf, co_r)
+        model.pop("_speeds_struct")
+        out["interference_and_cost_model"] = {
+            "per_free_cus": itf, "model": model,
+            "note": "alone = whole schedule on one stream, GEMMs on every compute unit; side_by_side = two streams "
+                    "with free_cus units left to the permutations; sigma, mu = time alone / time side by side. "
+                    "At free_cus = 0 mu is the time a permutation waits for a unit, not a co-run slowdown; the "
+                    "model takes sigma and mu from the best free_cus > 0",
+            "this_run": {"strategy": {0: "none", 2: "S4"}.get(args.reuse, "mode 1 (no row in Table II)"),
+                         "measured_step_ms": out["ms_per_step"]}}
     if not args.no_sweep:
         # the other workloads of the set, a few steps each, for the record
         others = []
@@ -403,7 +377,7 @@ def main():
         out["other_workloads"] = others
         # measured step of every strategy of Table II beside Eq. 10's prediction
         names = {0: "none", 2: "S4", 3: "S1", 4: "S2", 5: "S3"}
-        eq10 = out.get("interference_and_cost_model", {}).get("eq10", {})
+        eq10 = out.get("interference_and_cost_model", {}).get("model", {}).get("eq10", {})
         meas = {names[o["reuse_mode"]]: o["ms_per_step"] for o in others
                 if o["workload"] == out["config"]["workload"] and o["n_partitions"] == args.n and o["reuse_mode"] in names
                 and o["wgrad_group"] == 0}

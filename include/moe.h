@@ -100,6 +100,11 @@ typedef struct {
                                G partition-sized buffers each of T_DI, dT_DO, T_M and dT_M alive in
                                backward instead of two (one for T_M, dT_M).  Values above n count as
                                n.  Not with S1..S3. */
+    int32_t gemm_free_cus;  /* The bfloat16 expert GEMMs launch one persistent workgroup per compute unit,
+                               which leaves no room for a kernel of another stream until a GEMM ends.
+                               r > 0 launches them on r compute units fewer (rounded up to a multiple of 8,
+                               at least 8 stay), so that the permutation kernels of Section III-B's other
+                               stream run beside them on the units left free.  0: every unit. */
 } moe_config;
 
 /* Host only.  C_p = ceil(capacity_factor * k * (T / n) / E), evaluated in double

@@ -148,6 +148,7 @@ struct Dims {
     int renorm;      // combine weights are renormalised over the token's k choices
     int fuse;        // forward's first GEMM gathers its rows from the token-major input
     int G;           // partitions per weight-gradient GEMM in backward (>= 1)
+    int free_cus;    // compute units the persistent GEMM grids leave to other streams
     size_t es;   // element size in bytes
 };
 
@@ -213,6 +214,7 @@ struct GemmArgs {
     // after those of the partition before.  bf16 GEMM, at most 8.
     int k_segs;
     long long a_sstride, b_sstride;
+    int free_cus;         // bf16: compute units the persistent grid leaves free
     // epilogue operands
     void* Z;              // EPI_GELU: optional pre-activation out; EPI_DGELU: in/out
     int ldz;              // row stride of Z (elements); expert stride is Cp*ldz

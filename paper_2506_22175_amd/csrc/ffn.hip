@@ -15,6 +15,7 @@ static GemmArgs base_args(const Dims& d, const int* counts_p) {
     a.counts = counts_p;
     a.E = d.E;
     a.Cp = d.Cp;
+    a.free_cus = d.free_cus;
     return a;
 }
 

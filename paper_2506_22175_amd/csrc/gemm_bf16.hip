@@ -863,7 +863,9 @@ static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
     const int tiles_m = (Mmax + C::BM - 1) / C::BM, tiles_n = (a.N + C::BN - 1) / C::BN;
     int nblocks = a.E * tiles_m * tiles_n;
     nblocks = (nblocks + 7) / 8 * 8;
-    const int grid = nblocks < persistent_grid() ? nblocks : persistent_grid();
+    int full = persistent_grid() - (a.free_cus + 7) / 8 * 8;
+    if (full < 8) full = 8;
+    const int grid = nblocks < full ? nblocks : full;
     constexpr int lds = C::LDS_BYTES;
     auto kern = gemm_bf16_kernel<LAY, EPI, C>;
     static bool attr_done = false;
