@@ -105,6 +105,13 @@ typedef struct {
                                r > 0 launches them on r compute units fewer (rounded up to a multiple of 8,
                                at least 8 stay), so that the permutation kernels of Section III-B's other
                                stream run beside them on the units left free.  0: every unit. */
+    int32_t fuse_combine;   /* 1 (only with k = 1, the paper's own gate, Section IV-A): the second expert
+                               GEMM writes each kept row, times its combine weight, straight into its
+                               token's row of y, and the rows of dropped tokens are zeroed beforehand.
+                               Forward then runs no R kernel and keeps no T_DO (with fuse_gather: two
+                               GEMMs and no permutation per micro-batch); backward takes the
+                               combine-weight gradient in the GeLU-backward GEMM in every mode.  Not with
+                               S1..S3. */
 } moe_config;
 
 /* Host only.  C_p = ceil(capacity_factor * k * (T / n) / E), evaluated in double

@@ -43,14 +43,15 @@ class MoEConfig(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("M", ctypes.c_int32), ("H", ctypes.c_int32), ("E", ctypes.c_int32),
                 ("k", ctypes.c_int32), ("capacity_factor", ctypes.c_float), ("n_partitions", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("reuse", ctypes.c_int32), ("grad_overwrite", ctypes.c_int32), ("gate_renormalize", ctypes.c_int32),
-                ("fuse_gather", ctypes.c_int32), ("wgrad_group", ctypes.c_int32), ("gemm_free_cus", ctypes.c_int32)]
+                ("fuse_gather", ctypes.c_int32), ("wgrad_group", ctypes.c_int32), ("gemm_free_cus", ctypes.c_int32),
+                ("fuse_combine", ctypes.c_int32)]
 
 
 def make_config(T, M, H, E, k, capacity_factor, n_partitions=1, dtype=MOE_BF16, reuse=MOE_REUSE_NONE,
-                grad_overwrite=0, gate_renormalize=0, fuse_gather=0, wgrad_group=0, gemm_free_cus=0) -> MoEConfig:
+                grad_overwrite=0, gate_renormalize=0, fuse_gather=0, wgrad_group=0, gemm_free_cus=0, fuse_combine=0) -> MoEConfig:
     return MoEConfig(int(T), int(M), int(H), int(E), int(k), float(capacity_factor), int(n_partitions),
                      int(dtype), int(reuse), int(grad_overwrite), int(gate_renormalize), int(fuse_gather),
-                     int(wgrad_group), int(gemm_free_cus))
+                     int(wgrad_group), int(gemm_free_cus), int(fuse_combine))
 
 
 _lib = None

@@ -149,6 +149,7 @@ struct Dims {
     int fuse;        // forward's first GEMM gathers its rows from the token-major input
     int G;           // partitions per weight-gradient GEMM in backward (>= 1)
     int free_cus;    // compute units the persistent GEMM grids leave to other streams
+    int fcomb;       // k = 1: the second expert GEMM writes its weighted rows straight into y
     size_t es;   // element size in bytes
 };
 
@@ -195,7 +196,8 @@ enum GemmEpilogue {
     EPI_GELU = 1,       // Z = acc (optional), A = gelu(Z)
     EPI_DGELU = 2,      // dZ = w*acc*gelu'(Z), Z <- w*gelu(Z), dw_part = <gelu(Z), acc>
     EPI_ACCUM_F32 = 3,  // C(float) += acc
-    EPI_STORE_F32 = 4   // C(float) = acc (also where the reduction is empty)
+    EPI_STORE_F32 = 4,  // C(float) = acc (also where the reduction is empty)
+    EPI_SCATTER = 5     // C[c_rows[row]] = slot_w[row] * acc: rows leave for one matrix of c_row_limit rows
 };
 
 struct GemmArgs {
@@ -215,6 +217,8 @@ struct GemmArgs {
     int k_segs;
     long long a_sstride, b_sstride;
     int free_cus;         // bf16: compute units the persistent grid leaves free
+    const int* c_rows;    // EPI_SCATTER: [E*Cp] output row of each expert row (C is then one matrix for all
+    int c_row_limit;      //   experts, of c_row_limit rows; c_estride unused); slot_w gives the row weights
     // epilogue operands
     void* Z;              // EPI_GELU: optional pre-activation out; EPI_DGELU: in/out
     int ldz;              // row stride of Z (elements); expert stride is Cp*ldz
@@ -227,6 +231,7 @@ inline int gemm_prof_kind(int lay, int epi) {
     if (epi == EPI_GELU) return PK_GEMM_FWD1;
     if (epi == EPI_DGELU) return PK_GEMM_DGELU;
     if (epi == EPI_ACCUM_F32 || epi == EPI_STORE_F32) return PK_GEMM_WGRAD;
+    if (epi == EPI_SCATTER) return PK_GEMM_NN;
     return lay == GEMM_NN ? PK_GEMM_NN : PK_GEMM_DGRAD;
 }
 
@@ -238,8 +243,10 @@ int gemm_f32_dw_parts(int H);
 
 // ---- one partition's expert FFN (ffn.hip) ---------------------------------------
 // rows != NULL: DI is the token-major input [T, M] and rows[part] maps expert rows to its rows
+// y_rows != NULL (k = 1): the second GEMM writes slot_w * row into y[y_rows[...]] instead of DO
 moe_status ffn_fwd(const Dims& d, int part, const void* DI, const int* rows, const int* counts,
-                   const void* W1, const void* W2, void* Z, void* A, void* DO, hipStream_t s);
+                   const void* W1, const void* W2, void* Z, void* A, void* DO, hipStream_t s,
+                   const int* y_rows = nullptr, const float* slot_w = nullptr, void* y = nullptr);
 moe_status ffn_bwd(const Dims& d, int part, int recompute, const void* DI, void* Z, const void* dDO,
                    const int* counts, const float* slot_w, const void* W1, const void* W2,
                    void* dZ, void* dDI, float* dW1, float* dW2, float* dw_part, hipStream_t s);
@@ -251,5 +258,8 @@ moe_status ffn_bwd_main(const Dims& d, int part, int recompute, const void* DI, 
 moe_status ffn_wgrad(const Dims& d, int part, int nparts, int store, const void* DI, const void* A, const void* dDO,
                      const void* dZ, long long strideM, long long strideH, const int* counts,
                      float* dW1, float* dW2, hipStream_t s);
+
+// k = 1 with the fused combine: rows of y of dropped tokens <- 0 (permute.hip)
+moe_status zero_dropped(const Dims& d, const int* slot, void* y, hipStream_t s);
 
 }  // namespace moe

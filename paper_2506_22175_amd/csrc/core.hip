@@ -33,6 +33,9 @@ moe_status make_dims(const moe_config* cfg, Dims* d) {
     if (cfg->wgrad_group < 0 || cfg->wgrad_group > 8) return MOE_ERR_UNSUPPORTED;
     d->G = cfg->wgrad_group < 1 ? 1 : (cfg->wgrad_group > d->n ? d->n : cfg->wgrad_group);
     if (d->G > 1 && cfg->reuse > MOE_REUSE_RECOMPUTE) return MOE_ERR_UNSUPPORTED;   // not with the offloading strategies
+    if (cfg->fuse_combine != 0 && cfg->fuse_combine != 1) return MOE_ERR_UNSUPPORTED;
+    if (cfg->fuse_combine && (cfg->k != 1 || cfg->reuse > MOE_REUSE_RECOMPUTE)) return MOE_ERR_UNSUPPORTED;
+    d->fcomb = cfg->fuse_combine;
     if (cfg->gemm_free_cus < 0 || cfg->gemm_free_cus > 1024) return MOE_ERR_UNSUPPORTED;
     d->free_cus = cfg->gemm_free_cus;
     d->es = cfg->dtype == MOE_F32 ? 4 : 2;

@@ -42,6 +42,7 @@ struct EpiCtx {
     T* Z;            // pre-activation rows of this expert (ldz), may be null for EPI_GELU
     const float* w;  // slot weights of this expert's rows
     int ldc, ldz;
+    const int* out_rows;   // EPI_SCATTER: output row of each of this expert's rows; C is then the whole output
 };
 
 // v: four accumulators of row r, columns n..n+3 (all in range).  Returns this
@@ -74,6 +75,11 @@ __device__ __forceinline__ float epilogue4(const EpiCtx<T>& c, int r, int n, con
         Vec4<T>::store(c.C + (size_t)r * c.ldc + n, dz);
         Vec4<T>::store(c.Z + (size_t)r * c.ldz + n, a);
         return dot;
+    } else if constexpr (EPI == EPI_SCATTER) {
+        const float w = c.w[r];
+        const float o[4] = {w * v[0], w * v[1], w * v[2], w * v[3]};
+        Vec4<T>::store(c.C + (size_t)c.out_rows[r] * c.ldc + n, o);
+        return 0.0f;
     } else if constexpr (EPI == EPI_STORE_F32) {
         *reinterpret_cast<float4*>(c.Cf + (size_t)r * c.ldc + n) = make_float4(v[0], v[1], v[2], v[3]);
         return 0.0f;

@@ -20,7 +20,8 @@ static GemmArgs base_args(const Dims& d, const int* counts_p) {
 }
 
 moe_status ffn_fwd(const Dims& d, int part, const void* DI, const int* rows, const int* counts,
-                   const void* W1, const void* W2, void* Z, void* A, void* DO, hipStream_t s) {
+                   const void* W1, const void* W2, void* Z, void* A, void* DO, hipStream_t s,
+                   const int* y_rows, const float* slot_w, void* y) {
     const int* cp = counts + (size_t)part * d.E;
     // T_M = T_DI W1 ; A = gelu(T_M)
     GemmArgs a = base_args(d, cp);
@@ -37,6 +38,14 @@ moe_status ffn_fwd(const Dims& d, int part, const void* DI, const int* rows, con
     b.B = W2; b.ldb = d.M; b.b_estride = (long long)d.H * d.M;
     b.C = DO; b.ldc = d.M; b.c_estride = (long long)d.Cp * d.M;
     b.N = d.M; b.K = d.H;
+    if (y_rows) {
+        // one choice per token: a kept row is its token's whole output, weighted (Fig. 1: T_DO -> T_O with
+        // no T_DO in between)
+        b.C = y; b.c_estride = 0;
+        b.c_rows = y_rows + (size_t)part * d.Rp; b.c_row_limit = d.T;
+        b.slot_w = slot_w + (size_t)part * d.Rp;
+        return run_gemm(d, GEMM_NN, EPI_SCATTER, b, s);
+    }
     return run_gemm(d, GEMM_NN, EPI_STORE, b, s);
 }
 

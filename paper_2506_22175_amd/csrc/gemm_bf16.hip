@@ -676,9 +676,12 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
         constexpr int NPASS = TM * NCH;
         float* stage = reinterpret_cast<float*>(smem + C::STAGING_OFF + wid * (32 * CW * 4));
         constexpr int CES = (EPI == EPI_ACCUM_F32 || EPI == EPI_STORE_F32) ? 4 : 2;   // bytes per output element
-        const char* Cbase = (const char*)g.C + (size_t)e * g.c_estride * CES;
+        // (scattered rows: the whole output matrix, every row of which some tile may write)
+        const char* Cbase = EPI == EPI_SCATTER ? (const char*)g.C : (const char*)g.C + (size_t)e * g.c_estride * CES;
         const __amdgpu_buffer_rsrc_t rC = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<char*>(Cbase), 0, (unsigned)(((size_t)(Mdim - 1) * g.ldc + g.N) * CES), 0x00020000);
+            const_cast<char*>(Cbase), 0,
+            (unsigned)(((size_t)((EPI == EPI_SCATTER ? g.c_row_limit : Mdim) - 1) * g.ldc + g.N) * CES), 0x00020000);
+        const int* crows = g.c_rows ? g.c_rows + (size_t)e * g.Cp : nullptr;
         const bf16_t* Zbase = g.Z ? (const bf16_t*)g.Z + (size_t)e * g.Cp * g.ldz : nullptr;
         const __amdgpu_buffer_rsrc_t rZ = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<bf16_t*>(Zbase), 0, Zbase ? (unsigned)(((size_t)(Mdim - 1) * g.ldz + g.N) * 2) : 0u, 0x00020000);
@@ -686,8 +689,8 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
         const int erow = lane & 31, ehalf = lane >> 5;
         // What a pass reads from memory (the pre-activation and row weight for GeLU-backward, the old
         // sums for float accumulation) is requested one pass ahead.
-        constexpr bool READS = (EPI == EPI_DGELU || EPI == EPI_ACCUM_F32);
-        struct PassIn { uint4 zin[NPIECE]; float4 cin0[NPIECE], cin1[NPIECE]; float wrow[NPIECE]; };
+        constexpr bool READS = (EPI == EPI_DGELU || EPI == EPI_ACCUM_F32 || EPI == EPI_SCATTER);
+        struct PassIn { uint4 zin[NPIECE]; float4 cin0[NPIECE], cin1[NPIECE]; float wrow[NPIECE]; int crow[NPIECE]; };
         auto piece = [&](int ps, int t, int& m, int& c8, int& row, unsigned& oC, unsigned& oZ) {
             const int idx = lane + 64 * t;
             row = idx / CPRW; c8 = idx % CPRW;
@@ -704,6 +707,10 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                 piece(ps, t, m, c8, row, oC, oZ);
                 if constexpr (EPI == EPI_DGELU) {
                     in.zin[t] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rZ, oZ, 0, 0));
+                    in.wrow[t] = m < Mdim ? wbase[m] : 0.0f;
+                }
+                if constexpr (EPI == EPI_SCATTER) {
+                    in.crow[t] = m < Mdim ? crows[m] : -1;
                     in.wrow[t] = m < Mdim ? wbase[m] : 0.0f;
                 }
                 if constexpr (EPI == EPI_ACCUM_F32) {
@@ -753,6 +760,14 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                 if constexpr (EPI == EPI_STORE) {
                     uint4 o = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o), rC, oC, 0, 0);
+                } else if constexpr (EPI == EPI_SCATTER) {
+                    // the row's place in the output and its weight; rows and columns out of range are dropped
+                    const float w = in.wrow[t];
+                    const int n = n0 + wn * WN + (ps % NCH) * CW + c8 * 8;
+                    const unsigned oS = (in.crow[t] >= 0 && oC != OOB_OFFSET) ? (unsigned)(in.crow[t] * g.ldc + n) * 2u : OOB_OFFSET;
+                    uint4 o = make_uint4(pack_bf16x2(w * v[0], w * v[1]), pack_bf16x2(w * v[2], w * v[3]),
+                                         pack_bf16x2(w * v[4], w * v[5]), pack_bf16x2(w * v[6], w * v[7]));
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o), rC, oS, 0, 0);
                 } else if constexpr (EPI == EPI_GELU) {
                     float z[8], a[8];
 #pragma unroll
@@ -890,6 +905,7 @@ static moe_status launch_lay(GemmEpilogue epi, const GemmArgs& a, hipStream_t s)
         case EPI_DGELU: return launch_one<LAY, EPI_DGELU, typename CfgFor<LAY, EPI_DGELU>::type>(a, s);
         case EPI_ACCUM_F32: return launch_one<LAY, EPI_ACCUM_F32, typename CfgFor<LAY, EPI_ACCUM_F32>::type>(a, s);
         case EPI_STORE_F32: return launch_one<LAY, EPI_STORE_F32, typename CfgFor<LAY, EPI_STORE_F32>::type>(a, s);
+        case EPI_SCATTER: return launch_one<LAY, EPI_SCATTER, typename CfgFor<LAY, EPI_SCATTER>::type>(a, s);
     }
     return MOE_ERR_UNSUPPORTED;
 }
@@ -905,6 +921,10 @@ moe_status gemm_bf16(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStr
     const long long rmax = a.Cp > a.K ? a.Cp : a.K;
     if ((rmax + 8 * 64) * ldmax * 2 >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
     if (a.k_segs > 1 && (lay != GEMM_TN || a.k_segs > MAX_KSEGS)) return MOE_ERR_UNSUPPORTED;
+    if (epi == EPI_SCATTER) {
+        if (lay == GEMM_TN || !a.c_rows || !a.slot_w || a.c_row_limit <= 0) return MOE_ERR_UNSUPPORTED;
+        if (((long long)a.c_row_limit + 1) * a.ldc * 2 >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
+    }
     if (a.a_rows) {
         // gathered rows: only for the row operand of NN / NT, and the whole matrix must stay below 2 GiB
         if (lay == GEMM_TN || a.a_row_limit <= 0) return MOE_ERR_UNSUPPORTED;

@@ -73,8 +73,9 @@ __global__ __launch_bounds__(F_THREADS) void gemm_f32_kernel(GemmArgs g, int til
 
     EpiCtx<float> c;
     c.ldc = g.ldc; c.ldz = g.ldz;
-    c.C = (float*)g.C + (size_t)e * g.c_estride;
+    c.C = EPI == EPI_SCATTER ? (float*)g.C : (float*)g.C + (size_t)e * g.c_estride;
     c.Cf = c.C;
+    c.out_rows = g.c_rows ? g.c_rows + (size_t)e * g.Cp : nullptr;
     c.Z = g.Z ? (float*)g.Z + (size_t)e * g.Cp * g.ldz : nullptr;
     c.w = g.slot_w ? g.slot_w + (size_t)e * g.Cp : nullptr;
     const int n = n0 + tx * 4;
@@ -106,6 +107,7 @@ static moe_status launch_f32(GemmEpilogue epi, const GemmArgs& a, hipStream_t s)
         case EPI_DGELU: hipLaunchKernelGGL((gemm_f32_kernel<LAY, EPI_DGELU>), grid, block, 0, s, a, tiles_m, tiles_n); break;
         case EPI_ACCUM_F32: hipLaunchKernelGGL((gemm_f32_kernel<LAY, EPI_ACCUM_F32>), grid, block, 0, s, a, tiles_m, tiles_n); break;
         case EPI_STORE_F32: hipLaunchKernelGGL((gemm_f32_kernel<LAY, EPI_STORE_F32>), grid, block, 0, s, a, tiles_m, tiles_n); break;
+        case EPI_SCATTER: hipLaunchKernelGGL((gemm_f32_kernel<LAY, EPI_SCATTER>), grid, block, 0, s, a, tiles_m, tiles_n); break;
     }
     count_launch(LC_GEMM);
     MOE_CHECK_LAUNCH();
@@ -115,6 +117,7 @@ static moe_status launch_f32(GemmEpilogue epi, const GemmArgs& a, hipStream_t s)
 moe_status gemm_f32(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
     if (a.dw_part && a.dw_parts != gemm_f32_dw_parts(a.N)) return MOE_ERR_SHAPE;
     if (a.a_rows && (lay == GEMM_TN || a.a_row_limit <= 0)) return MOE_ERR_UNSUPPORTED;
+    if (epi == EPI_SCATTER && (lay == GEMM_TN || !a.c_rows || !a.slot_w || a.c_row_limit <= 0)) return MOE_ERR_UNSUPPORTED;
     if (lay == GEMM_NN) return launch_f32<GEMM_NN>(epi, a, s);
     if (lay == GEMM_NT) return launch_f32<GEMM_NT>(epi, a, s);
     return launch_f32<GEMM_TN>(epi, a, s);

@@ -56,10 +56,10 @@ static moe_status plan(const moe_config* cfg, const Dims& d, Workspace* w) {
     const int alive = d.G > 2 ? d.G : 2;
     // with the gathered first GEMM forward keeps no T_DI at all; backward dispatches into `alive` buffers
     w->nDI = ((reuse || d.fuse) && d.n > alive) ? alive : d.n;
-    w->nDO = (reuse && d.n > alive) ? alive : d.n;
+    w->nDO = d.fcomb ? 0 : (reuse && d.n > alive) ? alive : d.n;     // the fused combine keeps no T_DO
     w->nZ = mode_recomputes(d.reuse) ? d.G : mode_offloads_z(d.reuse) ? (d.n < 2 ? d.n : 2) : d.n;
-    w->ndDO = reuse ? w->nDO : (d.n > alive ? alive : d.n);
-    w->dDO_aliases_DO = reuse;
+    w->dDO_aliases_DO = reuse && !d.fcomb;
+    w->ndDO = w->dDO_aliases_DO ? w->nDO : (d.n > alive ? alive : d.n);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
     w->DI = take(w->bufM * w->nDI);
@@ -67,7 +67,7 @@ static moe_status plan(const moe_config* cfg, const Dims& d, Workspace* w) {
     w->Z = take(w->bufH * w->nZ);
     w->saved = off;
     w->HT = take(w->bufH * d.G);
-    w->dDO = reuse ? w->DO : take(w->bufM * w->ndDO);
+    w->dDO = w->dDO_aliases_DO ? w->DO : take(w->bufM * w->ndDO);
     w->dDI = take(w->bufM * 2);
     w->temp = off - w->saved;
     const size_t r0 = off;
@@ -83,7 +83,7 @@ static moe_status plan(const moe_config* cfg, const Dims& d, Workspace* w) {
     w->dL = take((size_t)d.T * d.E * sizeof(float));
     w->gate_scratch = take(gs);
     w->slot_scratch = take(ss);
-    w->rows = take(d.fuse ? (size_t)d.n * d.Rp * sizeof(int) : 0);
+    w->rows = take((d.fuse || d.fcomb) ? (size_t)d.n * d.Rp * sizeof(int) : 0);
     w->routing = off - r0;
     w->total = off;
     return MOE_OK;
@@ -118,13 +118,14 @@ static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace&
     MOE_TRY(moe_route(cfg, x, Wg, gate_bias, logits, topk_idx, topk_w, s0));
     MOE_TRY(moe_assign_slots(cfg, topk_idx, topk_w, slot, counts, (float*)(ws + w.slot_w),
                              ws + w.slot_scratch, s0));
-    const int* rows = d.fuse ? (const int*)(ws + w.rows) : nullptr;
-    if (d.fuse) MOE_TRY(moe_slot_rows(cfg, slot, (int*)(ws + w.rows), s0));
+    const int* rows = (d.fuse || d.fcomb) ? (const int*)(ws + w.rows) : nullptr;
+    if (rows) MOE_TRY(moe_slot_rows(cfg, slot, (int*)(ws + w.rows), s0));
+    if (d.fcomb) MOE_TRY(zero_dropped(d, slot, y, s0));
     HIP_TRY(hipEventRecord(evFork, s0));
     HIP_TRY(hipStreamWaitEvent(s1, evFork, 0));
 
     auto DIbuf = [&](int p) { return ws + w.DI + w.bufM * (p % w.nDI); };
-    auto DObuf = [&](int p) { return ws + w.DO + w.bufM * (p % w.nDO); };
+    auto DObuf = [&](int p) { return w.nDO ? ws + w.DO + w.bufM * (p % w.nDO) : nullptr; };
     auto Zbuf = [&](int p) { return ws + w.Z + w.bufH * (p % w.nZ); };
     const bool keepZ = !mode_recomputes(d.reuse);
 
@@ -143,13 +144,14 @@ static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace&
             }
             // C_p
             HIP_TRY(hipStreamWaitEvent(s1, evS[p], 0));
-            if (p >= w.nDO) HIP_TRY(hipStreamWaitEvent(s1, evR[p - w.nDO], 0));   // T_DO buffer free again
+            if (w.nDO && p >= w.nDO) HIP_TRY(hipStreamWaitEvent(s1, evR[p - w.nDO], 0));   // T_DO buffer free again
             if (off_z && p >= w.nZ) HIP_TRY(hipStreamWaitEvent(s1, evZout[p - w.nZ], 0));   // T_M buffer copied out
             // with recomputation T_M is not kept: the activated rows go to the one
             // shared H-wide buffer and the pre-activation is not written at all
             void* Aout = keepZ ? (void*)(ws + w.HT) : (void*)Zbuf(p);
-            MOE_TRY(ffn_fwd(d, p, d.fuse ? x : (const void*)DIbuf(p), rows, counts, W1, W2, keepZ ? Zbuf(p) : nullptr,
-                            Aout, DObuf(p), s1));
+            MOE_TRY(ffn_fwd(d, p, d.fuse ? x : (const void*)DIbuf(p), d.fuse ? rows : nullptr, counts, W1, W2,
+                            keepZ ? Zbuf(p) : nullptr, Aout, DObuf(p), s1,
+                            d.fcomb ? rows : nullptr, (const float*)(ws + w.slot_w), y));
             HIP_TRY(hipEventRecord(evC[p], s1));
             if (off_z) {
                 HIP_TRY(hipStreamWaitEvent(off->s2, evC[p], 0));
@@ -158,9 +160,10 @@ static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace&
             }
         }
         if (p >= 1) {
-            // R_{p-1}, issued after S_p so that S and R alternate on stream 0
+            // R_{p-1}, issued after S_p so that S and R alternate on stream 0 (with the fused combine
+            // C_{p-1} has written y itself and stream 0 only waits for it)
             HIP_TRY(hipStreamWaitEvent(s0, evC[p - 1], 0));
-            MOE_TRY(moe_combine(cfg, p - 1, DObuf(p - 1), slot, topk_w, y, s0));
+            if (!d.fcomb) MOE_TRY(moe_combine(cfg, p - 1, DObuf(p - 1), slot, topk_w, y, s0));
             HIP_TRY(hipEventRecord(evR[p - 1], s0));
         }
     }
@@ -185,11 +188,14 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
     hipEvent_t* evW = evIn + n;               // weight gradients of group g done
     hipEvent_t evFork = g_events[7 * (size_t)n];
     const bool reuse = d.reuse != MOE_REUSE_NONE;
+    // the combine-weight gradient: from the kept T_DO, or (T_DO overwritten or never written) from the
+    // GeLU-backward GEMM's row dots
+    const bool dw_in_gemm = reuse || d.fcomb;
     const bool recompute = mode_recomputes(d.reuse);
     const bool off_di = off && mode_offloads_di(d.reuse), off_z = off && mode_offloads_z(d.reuse);
 
     auto DIbuf = [&](int p) { return ws + w.DI + w.bufM * (p % w.nDI); };
-    auto DObuf = [&](int p) { return ws + w.DO + w.bufM * (p % w.nDO); };
+    auto DObuf = [&](int p) { return w.nDO ? ws + w.DO + w.bufM * (p % w.nDO) : nullptr; };
     auto Zbuf = [&](int p) { return ws + w.Z + w.bufH * (p % w.nZ); };
     auto dZbuf = [&](int p) { return ws + w.HT + w.bufH * (p % G); };
     auto dDObuf = [&](int p) { return ws + w.dDO + w.bufM * (p % w.ndDO); };
@@ -213,7 +219,7 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
             // its group, which come last.
             if (p >= w.ndDO) HIP_TRY(hipStreamWaitEvent(s0, evW[(p - w.ndDO) / G], 0));
             if (redispatch && p >= w.nDI && w.nDI != w.ndDO) HIP_TRY(hipStreamWaitEvent(s0, evW[(p - w.nDI) / G], 0));
-            if (reuse) {
+            if (dw_in_gemm) {
                 MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), nullptr, nullptr, s0));
                 if (redispatch) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
             } else {
@@ -237,7 +243,7 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
             HIP_TRY(hipStreamWaitEvent(s1, evS[p], 0));
             if (p >= 2) HIP_TRY(hipStreamWaitEvent(s1, evD[p - 2], 0));
             MOE_TRY(ffn_bwd_main(d, p, recompute ? 1 : 0, DIbuf(p), Zbuf(p), dDObuf(p), counts, slot_w, W1, W2,
-                                 dZbuf(p), dDIbuf(p), reuse ? dwpart(p) : nullptr, s1));
+                                 dZbuf(p), dDIbuf(p), dw_in_gemm ? dwpart(p) : nullptr, s1));
             HIP_TRY(hipEventRecord(evC[p], s1));
             // the weight gradients of a whole group after its last partition (Section III-B's per-partition
             // schedule when G = 1)
@@ -252,8 +258,8 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
             // S'_{p-1}: gate backward and rows of dDI back to token order
             const int q = p - 1;
             HIP_TRY(hipStreamWaitEvent(s0, evC[q], 0));
-            MOE_TRY(moe_gate_bwd(cfg, q, x, logits, topk_idx, slot, reuse ? nullptr : dw,
-                                 reuse ? dwpart(q) : nullptr, dL, dWg, ws + w.gate_scratch, s0));
+            MOE_TRY(moe_gate_bwd(cfg, q, x, logits, topk_idx, slot, dw_in_gemm ? nullptr : dw,
+                                 dw_in_gemm ? dwpart(q) : nullptr, dL, dWg, ws + w.gate_scratch, s0));
             MOE_TRY(moe_dispatch_bwd(cfg, q, dDIbuf(q), slot, dL, Wg, dx, s0));
             HIP_TRY(hipEventRecord(evD[q], s0));
         }

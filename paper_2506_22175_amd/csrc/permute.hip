@@ -159,6 +159,19 @@ __global__ __launch_bounds__(PERM_THREADS) void combine_kernel(
     }
 }
 
+// One choice per token and the combine fused into the second expert GEMM: a dropped token has no row
+// that would write its output, so its row of y is zeroed here.  One wavefront per token.
+template <typename T>
+__global__ __launch_bounds__(PERM_THREADS) void zero_dropped_kernel(const int* __restrict__ slot, T* __restrict__ y,
+                                                                    int Ttot, int M) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * PERM_WAVES + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (t >= Ttot || slot[t] >= 0) return;
+    const int U = M / Unit<T>::N;
+    uint4* out = reinterpret_cast<uint4*>(y + (size_t)t * M);
+    for (int c = lane; c < U; c += 64) out[c] = make_uint4(0, 0, 0, 0);
+}
+
 // dx[t] = sum_j dDI[slot[t,j]] + dL[t,:] Wg^T with the gate matrix transposed into LDS as
 // float (no conversion per token); a wavefront takes two tokens at a time, so each LDS read
 // feeds two tokens, and workgroups walk over the tokens.  Row e of W_g^T is stored so that the
@@ -765,6 +778,19 @@ extern "C" moe_status moe_combine(const moe_config* cfg, int32_t part, const voi
     MOE_CHECK_LAUNCH();
     return MOE_OK;
 }
+
+namespace moe {
+moe_status zero_dropped(const Dims& d, const int* slot, void* y, hipStream_t s) {
+    dim3 grid((d.T + PERM_WAVES - 1) / PERM_WAVES);
+    if (d.dtype == MOE_F32)
+        hipLaunchKernelGGL((zero_dropped_kernel<float>), grid, dim3(PERM_THREADS), 0, s, slot, (float*)y, d.T, d.M);
+    else
+        hipLaunchKernelGGL((zero_dropped_kernel<bf16_t>), grid, dim3(PERM_THREADS), 0, s, slot, (bf16_t*)y, d.T, d.M);
+    count_launch(LC_OTHER);
+    MOE_CHECK_LAUNCH();
+    return MOE_OK;
+}
+}  // namespace moe
 
 extern "C" moe_status moe_dispatch_bwd(const moe_config* cfg, int32_t part, const void* dDI, const int32_t* slot,
                                        const float* dL, const void* Wg, void* dx, void* stream) {

@@ -30,18 +30,18 @@ class LayerState:
 
     def __init__(self, T, M, H, E, k, capacity_factor, n_partitions=1, dtype="bf16", reuse=0, device="cuda:0",
                  second_stream: bool = True, grad_overwrite: int = 0, size_for_partitions=(),
-                 gate_renormalize: int = 0, fuse_gather: int = 0, wgrad_group: int = 0, gemm_free_cus: int = 0):
+                 gate_renormalize: int = 0, fuse_gather: int = 0, wgrad_group: int = 0, gemm_free_cus: int = 0, fuse_combine: int = 0):
         self.dtype = dtype
         self.device = device
         self.cfg = B.make_config(T, M, H, E, k, capacity_factor, n_partitions, _MOE_DT[dtype], reuse, grad_overwrite,
-                                 gate_renormalize, fuse_gather, wgrad_group, gemm_free_cus)
+                                 gate_renormalize, fuse_gather, wgrad_group, gemm_free_cus, fuse_combine)
         self.C_p = B.moe_capacity(self.cfg)
         self.ws_total, self.ws_saved, self.ws_temp, self.ws_routing = B.moe_workspace_bytes(self.cfg)
         ws_alloc, n_max = self.ws_total, n_partitions
         for n_alt in size_for_partitions:      # buffers that also fit these partition counts (granularity search)
             if T % n_alt == 0:
                 alt = B.make_config(T, M, H, E, k, capacity_factor, n_alt, _MOE_DT[dtype], reuse, grad_overwrite,
-                                    gate_renormalize, fuse_gather, wgrad_group, gemm_free_cus)
+                                    gate_renormalize, fuse_gather, wgrad_group, gemm_free_cus, fuse_combine)
                 ws_alloc = max(ws_alloc, B.moe_workspace_bytes(alt)[0])
                 n_max = max(n_max, n_alt)
         td = _TORCH_DT[dtype]
@@ -155,13 +155,13 @@ class LayerState:
 
 def run_layer_step(shape, inp: Dict[str, np.ndarray], n_partitions=1, reuse=0, poison=True,
                    second_stream=True, device="cuda:0", gate_renormalize=0, grad_overwrite=0,
-                   fuse_gather=0, wgrad_group=0, gemm_free_cus=0) -> Dict[str, np.ndarray]:
+                   fuse_gather=0, wgrad_group=0, gemm_free_cus=0, fuse_combine=0) -> Dict[str, np.ndarray]:
     """One step of the HIP path on a synth.MoEShape-like object; returns host arrays.  With
     grad_overwrite the weight-gradient buffers start as NaN instead of zero: the step must store them."""
     st = LayerState(shape.T, shape.M, shape.H, shape.E, shape.k, shape.capacity_factor, n_partitions,
                     shape.dtype, reuse, device, second_stream, grad_overwrite=grad_overwrite,
                     gate_renormalize=gate_renormalize, fuse_gather=fuse_gather, wgrad_group=wgrad_group,
-                    gemm_free_cus=gemm_free_cus)
+                    gemm_free_cus=gemm_free_cus, fuse_combine=fuse_combine)
     st.upload(inp)
     if poison:
         st.poison()

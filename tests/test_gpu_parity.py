@@ -439,6 +439,80 @@ def test_large_workload_sampled(oracle, runner):
 
 
 # ---------------------------------------------------------------------------------
+# one choice per token (the paper's own gate): the combine fused into the second expert GEMM
+# ---------------------------------------------------------------------------------
+
+K1_CASES = [
+    ("tiny", None, 1),
+    ("k1_bf16", (1024, 256, 512, 8, 1, 1.0, "bf16"), 2),
+    ("k1_bf16_heavy_drops", (1536, 264, 328, 6, 1, 0.5, "bf16"), 3),
+    ("k1_f32_ragged", (200, 72, 88, 5, 1, 0.8, "f32"), 2),
+    ("k1_dense_bf16", (300, 256, 512, 1, 1, 1.0, "bf16"), 1),
+]
+
+
+def _k1_shape(case):
+    name, dims, n = case
+    if dims is None:
+        return synth.WORKLOADS[name], n
+    T, M, H, E, k, cf, dt = dims
+    return synth.custom_shape(T, M, H, E, k, cf, dtype=dt, x_std=1.0, w_std=0.05, name=name), n
+
+
+@pytest.mark.parametrize("case", K1_CASES, ids=[c[0] for c in K1_CASES])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("gather", [0, 1])
+def test_fused_combine_full_parity(oracle, runner, case, mode, gather):
+    """k = 1: y[t] = w * (row of the second GEMM) written by that GEMM's epilogue, zeros for dropped tokens,
+    no T_DO anywhere; backward takes the combine-weight gradient from the GeLU-backward GEMM in every mode."""
+    s, n = _k1_shape(case)
+    d = synth.make_inputs(s, seed=12)
+    r = _oracle(oracle, s, d, n)
+    g = runner.run_layer_step(s, d, n, mode, fuse_combine=1, fuse_gather=gather)
+    _check_routing(g, r)
+    names = ["y", "dx", "dW1", "dW2"] + (["dWg"] if np.abs(r["dWg"]).max() > 1e-12 else [])
+    _check_values(g, r, TOL[s.dtype], names=tuple(names))
+    dropped = (r["slot"] < 0).all(axis=1)
+    if dropped.any():
+        assert np.all(g["y"][dropped] == 0.0) and np.all(g["dx"][dropped] == 0.0)
+    if "drops" in case[0]:
+        assert dropped.mean() > 0.2
+    plain = runner.run_layer_step(s, d, n, mode, fuse_gather=gather)
+    if s.dtype == "f32":
+        assert np.array_equal(g["y"], plain["y"])        # w * row in float either way
+    else:
+        assert relerr(g["y"], plain["y"]) <= 1e-2         # one rounding to bfloat16 fewer
+
+
+def test_fused_combine_runs_no_permutation_in_forward_and_keeps_no_T_DO(runner):
+    from paper_2506_22175_amd import binding as B
+    s, n = _k1_shape(K1_CASES[1])
+    d = synth.make_inputs(s, seed=0)
+    for mode in (0, 2):
+        st = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, n, s.dtype, mode, fuse_gather=1, fuse_combine=1)
+        base = runner.LayerState(s.T, s.M, s.H, s.E, s.k, s.capacity_factor, n, s.dtype, mode, fuse_gather=1)
+        st.upload(d)
+        st.zero_grads()
+        B.moe_launch_counts(reset=True)
+        st.forward()
+        torch.cuda.synchronize()
+        gemms, perms, _ = B.moe_launch_counts(reset=True)
+        assert (gemms, perms) == (2 * n, 0)
+        st.backward()
+        torch.cuda.synchronize()
+        gemms, perms, _ = B.moe_launch_counts(reset=True)
+        assert (gemms, perms) == ((5 if mode == 2 else 4) * n, 3 * n)
+        if mode == 0:
+            # T_DO of every partition is gone from what forward keeps for backward
+            Rp = st.C_p * s.E
+            assert base.ws_saved - st.ws_saved == n * Rp * s.M * 2
+    with pytest.raises(B.MoEError) as e:                  # two choices per token: a row is not the whole output
+        s2 = synth.WORKLOADS["small"]
+        runner.LayerState(s2.T, s2.M, s2.H, s2.E, s2.k, s2.capacity_factor, 2, s2.dtype, 2, fuse_combine=1)
+    assert e.value.status == 3
+
+
+# ---------------------------------------------------------------------------------
 # weight gradients of several partitions in one GEMM (wgrad_group)
 # ---------------------------------------------------------------------------------
 
