@@ -48,15 +48,23 @@ def cpu_baseline(shape, inp, budget_tokens):
 
 def recorded_traffic(workload, n, reuse):
     """HBM-side bytes per GEMM launch recorded from rocprofv3 --pmc runs (FETCH_SIZE +
-    WRITE_SIZE, calibrated on the dispatch kernel); None if no record for this setup."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}_n{n}_reuse{reuse}.txt")
+    WRITE_SIZE, calibrated on the dispatch kernel) and where the record is; (None, None) if
+    there is none for this setup.  A recorded value, not a measurement of this run: counters
+    need runs of their own."""
+    name = f"hbm_traffic_{workload}_n{n}_reuse{reuse}.txt"
+    path = os.path.join(ROOT, "profiles", name)
     try:
+        val, date = None, "undated"
         for line in open(path):
             if line.startswith("gemm_traffic_bytes_per_launch"):
-                return float(line.split()[1])
+                val = float(line.split()[1])
+            if line.startswith("recorded "):
+                date = line.split(None, 1)[1].strip()
+        if val is not None:
+            return val, f"recorded by rocprofv3 --pmc, profiles/{name} ({date}); not measured in this run"
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0, group=0):
@@ -137,7 +145,8 @@ def measure(args, workload, n, reuse, steps, warmup, brief=False, fuse=0, group=
     roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (grouped expert GEMM, all layouts)",
                 "achieved": achieved_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved_tflops / PEAK_BF16_TFLOPS,
-                "traffic": recorded_traffic(workload, n, reuse),
+                "traffic": recorded_traffic(workload, n, reuse)[0] if not group else None,
+                "traffic_source": recorded_traffic(workload, n, reuse)[1] if not group else None,
                 "launches": g_launch, "avg_launch_us": 1e3 * g_ms / max(g_launch, 1),
                 "flop_per_launch": g_flop_per_step * steps / max(g_launch, 1), "per_use": per_kind,
                 "kernel_timing": kernel_timing}

@@ -49,6 +49,15 @@ def test_argument_errors_are_status_codes():
         # the strategies that copy forward's T_DI to the host need a T_DI in forward
         (B.make_config(256, 64, 128, 4, 1, 1.0, 2, B.MOE_BF16, B.MOE_REUSE_S1, fuse_gather=1), 3),
         (B.make_config(256, 64, 128, 4, 1, 1.0, 2, B.MOE_BF16, B.MOE_REUSE_S3, fuse_gather=1), 3),
+        # grouped weight gradients: at most eight partitions, not with the offloading strategies
+        (B.make_config(256, 64, 128, 4, 1, 1.0, 2, wgrad_group=9), 3),
+        (B.make_config(256, 64, 128, 4, 1, 1.0, 2, wgrad_group=-1), 3),
+        (B.make_config(256, 64, 128, 4, 1, 1.0, 2, B.MOE_BF16, B.MOE_REUSE_S2, wgrad_group=2), 3),
+        # the fused combine needs one choice per token
+        (B.make_config(256, 64, 128, 4, 2, 1.0, 2, fuse_combine=1), 3),
+        (B.make_config(256, 64, 128, 4, 1, 1.0, 2, fuse_combine=2), 3),
+        (B.make_config(256, 64, 128, 4, 1, 1.0, 2, B.MOE_BF16, B.MOE_REUSE_S1, fuse_combine=1), 3),
+        (B.make_config(256, 64, 128, 4, 1, 1.0, 2, gemm_free_cus=-8), 3),
     ]
     for cfg, code in bad:
         with pytest.raises(B.MoEError) as ei:
@@ -90,3 +99,35 @@ def test_workspace_follows_the_memory_model(oracle):
             cfg = B.make_config(T, M, H, E, k, cf, n, B.MOE_BF16, mode, fuse_gather=1)
             saved_f = B.moe_workspace_bytes(cfg)[1]
             assert saved_f == sizes[mode] - (bufM * (n - 2) if (mode == 0 and n > 2) else 0)
+
+
+def test_workspace_with_grouped_weight_gradients_and_fused_combine(oracle):
+    """wgrad_group = G keeps G partition buffers of T_DI, dT_DO (which alias T_DO in the shared-buffer modes),
+    T_M (with recomputation) and dT_M alive in backward; the fused combine keeps no T_DO.  In buffer counts:"""
+    T, M, H, E, k, cf = 16384, 1024, 4096, 8, 2, 1.25
+    for n in (2, 4, 8):
+        R_p = oracle.capacity(T, E, k, cf, n) * E
+        bufM, bufH = 2 * R_p * M, 2 * R_p * H
+        for G in (1, 2, 4, 8):
+            g = min(G, n)
+            alive = max(2, g)
+            cfg = B.make_config(T, M, H, E, k, cf, n, B.MOE_BF16, 2, wgrad_group=G)
+            total, saved, temp, routing = B.moe_workspace_bytes(cfg)
+            nbuf = alive if n > alive else n
+            assert saved == 2 * nbuf * bufM + g * bufH              # T_DI and T_DO buffers, T_M buffers
+            assert temp == g * bufH + 2 * bufM                      # dT_M buffers, two dT_DI (dT_DO aliases T_DO)
+            plain = B.moe_workspace_bytes(B.make_config(T, M, H, E, k, cf, n, B.MOE_BF16, 2))
+            assert total >= plain[0] and (G == 1) == (total == plain[0]) or g == 1
+        # G larger than n counts as n
+        assert B.moe_workspace_bytes(B.make_config(T, M, H, E, k, cf, n, B.MOE_BF16, 2, wgrad_group=8)) == \
+            B.moe_workspace_bytes(B.make_config(T, M, H, E, k, cf, n, B.MOE_BF16, 2, wgrad_group=min(8, n)))
+    # one choice per token
+    k = 1
+    for n in (1, 4):
+        R_p = oracle.capacity(T, E, k, cf, n) * E
+        bufM = 2 * R_p * M
+        for mode in (0, 1, 2):
+            a = B.moe_workspace_bytes(B.make_config(T, M, H, E, k, cf, n, B.MOE_BF16, mode))
+            f = B.moe_workspace_bytes(B.make_config(T, M, H, E, k, cf, n, B.MOE_BF16, mode, fuse_combine=1))
+            n_do = n if (mode == 0 or n <= 2) else 2
+            assert a[1] - f[1] == n_do * bufM                       # no T_DO among what forward keeps
