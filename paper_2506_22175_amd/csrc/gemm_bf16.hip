@@ -63,12 +63,11 @@ __device__ __forceinline__ unsigned lds_address(const char* p) {
 }
 
 // ---- tile shape ------------------------------------------------------------------
-// Three main loops:
-//   LOOP_RING2  ring of two stages, compiler-scheduled;
-//   LOOP_PIPE32 ring of five stages of 32 k, hand-scheduled (one or two waves per SIMD);
-//   LOOP_W64    hand-scheduled 64-k steps with one ring per operand: a K-contiguous operand
-//               travels as whole 128-byte lines (units of 64 k), the other one in tiles of 32 k.
-enum { LOOP_RING2 = 0, LOOP_PIPE32 = 1, LOOP_W64 = 2 };
+// Two main loops, both hand-scheduled:
+//   LOOP_PIPE32 ring of five stages of 32 k;
+//   LOOP_W64    64-k steps with one ring per operand: a K-contiguous operand travels as whole
+//               128-byte lines (units of 64 k), the other one in tiles of 32 k.
+enum { LOOP_PIPE32 = 1, LOOP_W64 = 2 };
 template <int BM_, int BN_, int BK_, int NS_, int WAVES_M_, int WAVES_N_, int OCC_, int LOOP_>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, NS = NS_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
@@ -86,7 +85,6 @@ struct TileCfg {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds the CU's 160 KB");
     static_assert(BK == 32 || BK == 64, "tile depth");
     static_assert(LOOP != LOOP_PIPE32 || (BK == 32 && NS == 5), "the hand-scheduled ring is five stages of 32 k");
-    static_assert(LOOP != LOOP_RING2 || NS == 2, "two stages");
     static_assert(LOOP != LOOP_W64 || (BM == 256 && BN == 256 && BK == 64 && WAVES_M == 2 && WAVES_N == 2 && OCC == 1),
                   "the two-ring loop is written for four waves of 128 x 128");
 };
@@ -296,7 +294,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     // The epilogue stages accumulators in the first SB stages of the ring; a tile's ring
     // starts at stage SB, so that its first operand tiles can arrive during the epilogue
     // of the tile before.  (Two-ring loop: in the third unit of the wide ring.)
-    constexpr int SB = C::PIPE ? 2 : 1;
+    constexpr int SB = 2;
     constexpr int CW = C::CW;
     static_assert(W64 || C::WAVES * 32 * CW * 4 <= SB * STAGE, "staging does not fit below the ring's first stage");
     static_assert(!W64 || C::WAVES * 32 * CW * 4 <= 32 * 1024, "staging does not fit one unit of the wide ring");
@@ -434,21 +432,18 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
             for (int l = 0; l < NL; ++l) load_narrow(ta_, tb_, 2, 2, l);
 #pragma unroll
             for (int l = 0; l < NL / 2; ++l) load_narrow(ta_, tb_, 3, 3, l);
-        } else if constexpr (C::PIPE) {
+        } else {
 #pragma unroll
             for (int s = 0; s < 3; ++s)
 #pragma unroll
                 for (int l = 0; l < LPW; ++l) request(tc, kc_, ta_, tb_, smem + (SB + s) * STAGE, s * BK, l);
-        } else {
-            ta_.load(smem + SB * STAGE, 0, wid);
-            tb_.load(smem + SB * STAGE + A_BYTES, 0, wid);
         }
     };
     auto issue_late = [&](const TileCoord& tc, KCursor& kc_, AT& ta_, BT& tb_) {
         if constexpr (W64) {
 #pragma unroll
             for (int l = 0; l < WL / 4; ++l) load_wide(ta_, tb_, 2, 2, l);
-        } else if constexpr (C::PIPE) {
+        } else {
 #pragma unroll
             for (int l = 0; l < LPW; ++l) request(tc, kc_, ta_, tb_, smem, 3 * BK, l);
 #pragma unroll
@@ -558,7 +553,7 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
                 n4 = n4b;
             }
             asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-        } else if constexpr (C::PIPE) {
+        } else {
             // Hand-scheduled loop (with one wave per SIMD nothing else hides a stall): every
             // LDS read and every load into LDS sits between two matrix instructions, one per
             // instruction, and the data a block of TM x TN matrix instructions needs was
@@ -615,36 +610,6 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
             // the assembler-level matrix instructions are invisible to the compiler's hazard
             // checks: let the last of them retire before anything reads the accumulators
             asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-        } else {
-            // Ring of two stages.  In iteration kt the wave waits until its own part of tile
-            // kt has landed, the barrier makes every wave's part visible and tells that tile
-            // kt-1 has been consumed, whose stage then receives tile kt+1.  A tile past the
-            // end reads as zeros.
-            int st_cur = SB, st_free = SB ^ 1;
-            for (int kt = 0; kt < KT; ++kt) {
-                if (kt > 0 || first) wait_vmcnt<0>();                // (a later tile's tile 0: waited for at the handover)
-                __builtin_amdgcn_s_barrier();
-                asm volatile("" ::: "memory");
-                char* cs = smem + st_cur * STAGE;
-                char* nxt = smem + st_free * STAGE;
-                ta.load(nxt, (kt + 1) * BK, wid);
-                tb.load(nxt + A_BYTES, (kt + 1) * BK, wid);
-#pragma unroll
-                for (int kk = 0; kk < BK / 16; ++kk) {
-                    bf16x8 af[TM], bfr[TNN];
-#pragma unroll
-                    for (int i = 0; i < TM; ++i) af[i] = fa[i].read(cs, kk);
-#pragma unroll
-                    for (int j = 0; j < TNN; ++j) bfr[j] = fb[j].read(cs + A_BYTES, kk);
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TNN; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-                }
-                st_free = st_cur;
-                st_cur ^= 1;
-            }
         }
         wait_vmcnt<0>();                             // nothing of this workgroup is in flight into LDS any more
         __builtin_amdgcn_s_barrier();                // and every wave is done reading the ring
@@ -842,9 +807,9 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
 //          the number of requests; here every request but those of NT's row operand is a whole line.
 //   Cfg4   ring of 5 x 32 k: the weight-gradient GEMMs (TN), whose two operands are N-contiguous
 //          and come in whole lines anyway.
-// (The loops with two waves per SIMD, hand-scheduled or compiler-scheduled, remain selectable through
-// TileCfg: their GeLU epilogues run faster, their main loops read half as much again from LDS and lose
-// more than that.)
+// (Shapes with two waves of 128 x 64 per SIMD - TileCfg<256, 256, 32, 5, 2, 4, 2, LOOP_PIPE32> - ran the GeLU
+// epilogues faster and the main loops slower, reading half as much again from LDS; with the cheaper GeLU
+// arithmetic the four-wave shapes win everywhere.)
 typedef TileCfg<256, 256, 32, 5, 2, 2, 1, LOOP_PIPE32> Cfg4;
 typedef TileCfg<256, 256, 64, 3, 2, 2, 1, LOOP_W64> CfgW;
 template <int LAY, int EPI> struct CfgFor { typedef CfgW type; };

@@ -282,27 +282,38 @@ __global__ __launch_bounds__(DXF_THREADS) void dispatch_bwd_f32lds_kernel(
 typedef short bf16x4_hw __attribute__((ext_vector_type(4)));
 typedef float f32x4_hw __attribute__((ext_vector_type(4)));
 constexpr int DXM_TOK = 16;          // tokens per token group
-constexpr int DXM_TG = 2;            // token groups per workgroup (they share the gate weights in LDS)
+constexpr int DXM_CT = 64;           // column threads of a workgroup: one wavefront, 512 columns
+constexpr int DXM_TG = 8;            // token groups per workgroup, one wavefront each (they share the gate weights in LDS)
 template <int EG>                    // expert groups of four: E <= 4*EG
-__global__ __launch_bounds__(PERM_THREADS * DXM_TG, 2) void dispatch_bwd_mfma_kernel(
+__global__ __launch_bounds__(DXM_CT * DXM_TG, 2) void dispatch_bwd_mfma_kernel(
     const bf16_t* __restrict__ dDI, const int* __restrict__ slot, const float* __restrict__ dL,
     const bf16_t* __restrict__ Wg, bf16_t* __restrict__ dx, int t_begin, int t_count, int M, int E, int k) {
-    const int ct = threadIdx.x % PERM_THREADS;                       // column thread
-    const int tg = __builtin_amdgcn_readfirstlane(threadIdx.x / PERM_THREADS);
-    const int c = (blockIdx.x * PERM_THREADS + ct) * 8;
+    const int ct = threadIdx.x % DXM_CT;                       // column thread
+    const int tg = __builtin_amdgcn_readfirstlane(threadIdx.x / DXM_CT);
+    const int c = (blockIdx.x * DXM_CT + ct) * 8;
     const bool c_ok = c < M;                       // lanes beyond the row still feed the A operand
     const int lane = threadIdx.x & 63;
     const int tl0 = min((blockIdx.y * DXM_TG + tg) * DXM_TOK, t_count);
     const int tl1 = min(tl0 + DXM_TOK, t_count);
-    // rows of four tokens, choices j0 and j0 + 1: eight 16-byte reads in flight per lane
-    auto request = [&](int tb, int j0, uint4 (&raw)[4][2]) {
+    // The slots of the group's (token, choice) pairs, one per lane (two registers cover 16 tokens x 8
+    // choices); a pair's slot is then broadcast from its lane, which costs no memory access per row.
+    const int nsl = (tl1 - tl0) * k;
+    const int* sl0 = slot + (size_t)(t_begin + tl0) * k;
+    const int sv0 = lane < nsl ? sl0[lane] : -1;
+    const int sv1 = lane + 64 < nsl ? sl0[lane + 64] : -1;
+    const int cc = c_ok ? c : 0;
+    // rows of four tokens, choices j0 and j0 + 1: eight 16-byte reads in flight per lane, no branch
+    // around them (a missing row is read from row 0 and replaced by zeros)
+    auto request = [&](int tb, int j0, uint4 (&raw)[4][2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj) {
-                const int sj = (tb + u < tl1 && j0 + jj < k) ? slot[(size_t)(t_begin + tb + u) * k + j0 + jj] : -1;
-                raw[u][jj] = make_uint4(0, 0, 0, 0);
-                if (c_ok && sj >= 0) raw[u][jj] = ld_row<true>(reinterpret_cast<const uint4*>(dDI + (size_t)sj * M + c));
+                const int i = (tb - tl0 + u) * k + j0 + jj;
+                const int s0 = __builtin_amdgcn_readlane(sv0, i & 63), s1 = __builtin_amdgcn_readlane(sv1, i & 63);
+                const int sj = (tb + u < tl1 && j0 + jj < k) ? (i < 64 ? s0 : s1) : -1;
+                const uint4 v = ld_row<true>(reinterpret_cast<const uint4*>(dDI + (size_t)max(sj, 0) * M + cc));
+                raw[u][jj] = sj >= 0 ? v : make_uint4(0, 0, 0, 0);
             }
     };
     // gate gradients of this lane's token (tb + lane%4) for the A operand
@@ -324,35 +335,43 @@ __global__ __launch_bounds__(PERM_THREADS * DXM_TG, 2) void dispatch_bwd_mfma_ke
             }
         }
     };
-    uint4 raw[4][2];
-    float4 dl[EG];
-    request_dl(tl0, dl);                           // the first round's rows travel during the prologue
-    request(tl0, 0, raw);
-
     // Gate weights of this workgroup's columns into LDS with coalesced 16-byte reads.  A lane's
     // piece (64*EG bytes: 8 columns x 4*EG experts) is padded by 16 bytes so that the reads of a
-    // wavefront spread over all banks.
+    // wavefront spread over all banks.  The weights are staged before the first rows are requested:
+    // an LDS write waits for every load issued before it, and the rows take several times longer
+    // to arrive than the weights.
     extern __shared__ __attribute__((aligned(16))) char dxm_smem[];
     constexpr int CHUNK = 64 * EG;
     constexpr int PITCH = CHUNK + 16;
-    {
-        const int c_base = blockIdx.x * PERM_THREADS * 8;
-        const int ncols = min(PERM_THREADS * 8, M - c_base);
-        if (E == 4 * EG) {
-            const uint4* src = reinterpret_cast<const uint4*>(Wg + (size_t)c_base * E);
-            const int pieces = ncols * EG / 2;                        // 16-byte pieces of the slice
-            for (int q = threadIdx.x; q < pieces; q += PERM_THREADS * DXM_TG) {
-                const int byte = q * 16;
-                *reinterpret_cast<uint4*>(dxm_smem + (byte / CHUNK) * PITCH + byte % CHUNK) = src[q];
-            }
-        } else {
-            for (int q = threadIdx.x; q < ncols * 4 * EG; q += PERM_THREADS * DXM_TG) {
-                const int col = q / (4 * EG), e = q % (4 * EG);
-                const bf16_t v = e < E ? Wg[(size_t)(c_base + col) * E + e] : (bf16_t)0;
-                *reinterpret_cast<bf16_t*>(dxm_smem + (col / 8) * PITCH + (col % 8) * 8 * EG + e * 2) = v;
-            }
+    const int c_base = blockIdx.x * DXM_CT * 8;
+    const int ncols = min(DXM_CT * 8, M - c_base);
+    const int pieces = ncols * EG / 2;             // 16-byte pieces of the slice: at most two per thread
+    static_assert(DXM_CT * 8 * 4 / 2 <= 2 * DXM_CT * DXM_TG, "two pieces per thread cover the slice");
+    const bool whole = E == 4 * EG;
+    uint4 piece[2];
+    if (whole) {
+        const uint4* src = reinterpret_cast<const uint4*>(Wg + (size_t)c_base * E);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) piece[i] = src[min((int)threadIdx.x + i * DXM_CT * DXM_TG, pieces - 1)];
+    }
+    if (whole) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int q = threadIdx.x + i * DXM_CT * DXM_TG;
+            const int byte = q * 16;
+            if (q < pieces) *reinterpret_cast<uint4*>(dxm_smem + (byte / CHUNK) * PITCH + byte % CHUNK) = piece[i];
+        }
+    } else {
+        for (int q = threadIdx.x; q < ncols * 4 * EG; q += DXM_CT * DXM_TG) {
+            const int col = q / (4 * EG), e = q % (4 * EG);
+            const bf16_t v = e < E ? Wg[(size_t)(c_base + col) * E + e] : (bf16_t)0;
+            *reinterpret_cast<bf16_t*>(dxm_smem + (col / 8) * PITCH + (col % 8) * 8 * EG + e * 2) = v;
         }
     }
+    uint4 raw[4][2];
+    float4 dl[EG];
+    request_dl(tl0, dl);
+    request(tl0, 0, raw);
     __syncthreads();
     for (int tb = tl0; tb < tl1; tb += 4) {
         if (tb > tl0) {
@@ -474,76 +493,24 @@ __global__ __launch_bounds__(PERM_THREADS) void dispatch_bwd_kernel(
 }
 
 // ---- gate backward ------------------------------------------------------------
-
-// dL[t,e] = p[t,e] * (dp[t,e] - sum_e' dp[t,e'] p[t,e']) with dp nonzero only at the
-// chosen experts; one thread per token.
-__device__ __forceinline__ void gate_dl_token(
-    const float* __restrict__ logits, const int* __restrict__ topk_idx, const float* dw_t,
-    float* __restrict__ dL, float* sdl, int t, int E, int k, int renorm) {
-    const float* lg = logits + (size_t)t * E;
-    float mx = -INFINITY;
-    for (int e = 0; e < E; ++e) mx = fmaxf(mx, lg[e]);
-    float g[8];
-    int ids[8];
-    for (int j = 0; j < k; ++j) {
-        ids[j] = topk_idx[(size_t)t * k + j];
-        g[j] = dw_t[j];
-    }
-    if (renorm) {
-        // weights are a softmax over the chosen logits only: dL_e = w_j (dw_j - sum_j' dw_j' w_j')
-        // for a chosen e, zero otherwise
-        float den = 0.0f;
-        for (int j = 0; j < k; ++j) den += expf(lg[ids[j]] - mx);
-        const float inv = 1.0f / den;
-        float inner = 0.0f;
-        for (int j = 0; j < k; ++j) inner = fmaf(g[j], expf(lg[ids[j]] - mx) * inv, inner);
-        for (int e = 0; e < E; ++e) {
-            float v = 0.0f;
-            for (int j = 0; j < k; ++j)
-                if (ids[j] == e) v = expf(lg[e] - mx) * inv * (g[j] - inner);
-            dL[(size_t)t * E + e] = v;
-            sdl[e] = v;
-        }
-        return;
-    }
-    float sum = 0.0f;
-    for (int e = 0; e < E; ++e) sum += expf(lg[e] - mx);
-    const float inv = 1.0f / sum;
-    float inner = 0.0f;
-    for (int j = 0; j < k; ++j) inner = fmaf(g[j], expf(lg[ids[j]] - mx) * inv, inner);
-    for (int e = 0; e < E; ++e) {
-        float p = expf(lg[e] - mx) * inv;
-        float dp = 0.0f;
-        for (int j = 0; j < k; ++j) if (ids[j] == e) dp = g[j];
-        const float v = p * (dp - inner);
-        dL[(size_t)t * E + e] = v;
-        sdl[e] = v;
-    }
-}
-
-// One workgroup takes DWG_TOK tokens: first dL of those tokens (to global memory for the
-// dispatch-backward kernel, and to LDS), then part[b][d][e] = sum over the tokens of
-// x[t,d] * dL[t,e], each thread owning eight columns d.
+//
+// dL[t,e] = p[t,e] * (dp[t,e] - sum_e' dp[t,e'] p[t,e']) with dp nonzero only at the chosen
+// experts (the softmax Jacobian applied to the combine-weight gradients), then
+// dWg += x^T dL.  A workgroup of 256 threads prepares dL for a block of DWG_TOK tokens, four
+// lanes per token.
 constexpr int DWG_TOK = 64;
 constexpr int DWG_EMAX = 64;
-template <typename T>
-__global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
-    const T* __restrict__ x, const float* __restrict__ logits, const int* __restrict__ topk_idx,
-    const int* __restrict__ slot, const float* __restrict__ dw, const float* __restrict__ dw_part, int parts,
-    float* __restrict__ dL, float* __restrict__ part, int t_begin, int t_count, int M, int E, int k, int renorm) {
-    // dL of the block's tokens; rows of missing tokens and columns from E up to the next
-    // multiple of 16 stay zero, so the product loop below needs no predicates
-    __shared__ __attribute__((aligned(16))) float sdl[DWG_TOK][DWG_EMAX + 4];
-    for (int q = threadIdx.x; q < DWG_TOK * (DWG_EMAX + 4); q += PERM_THREADS) (&sdl[0][0])[q] = 0.0f;
-    const int tl0 = blockIdx.y * DWG_TOK;
-    const int nt = min(DWG_TOK, t_count - tl0);
-    // combine-weight gradients of the block's (token, choice) pairs: either given, or the
-    // fixed-order sum of the GEMM epilogue's column-block partial sums (four lanes per pair)
-    __shared__ float sdw[DWG_TOK * 8];
+constexpr int DWG_LD = DWG_EMAX + 4;     // floats per row of the block's LDS tile
+
+// Combine-weight gradients of the block's (token, choice) pairs into sdw[ti*k + j]: either given,
+// or the fixed-order sum of the GEMM epilogue's column-block partial sums (four lanes per pair).
+__device__ __forceinline__ void gate_block_dw(
+    float* sdw, const int* __restrict__ slot, const float* __restrict__ dw, const float* __restrict__ dw_part,
+    int parts, int t_first, int nt, int k) {
     for (int q = threadIdx.x; q < nt * k * 4; q += PERM_THREADS) {
         const int pair = q >> 2, sub = q & 3;
         const int ti = pair / k, j = pair - ti * k;
-        const int t = t_begin + tl0 + ti;
+        const int t = t_first + ti;
         float v = 0.0f;
         if (dw_part) {
             const int sl = slot[(size_t)t * k + j];
@@ -575,9 +542,107 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
         v += __shfl_xor(v, 2, 64);
         if (sub == 0) sdw[pair] = v;
     }
+}
+
+// The block's logits (nt rows of E floats, contiguous in memory) into the LDS tile.
+__device__ __forceinline__ void gate_block_logits(float (*tile)[DWG_LD], const float* __restrict__ logits,
+                                                  int t_first, int nt, int E) {
+    const float* src = logits + (size_t)t_first * E;
+    for (int q = threadIdx.x; q < nt * E; q += PERM_THREADS) tile[q / E][q % E] = src[q];
+}
+
+// The experts chosen by the token of this thread (thread / 4 within the block), -1 beyond k or past the
+// last token; requested first so that the read is over by the time gate_block_dl needs it.
+__device__ __forceinline__ void gate_block_ids(int (&ids)[8], const int* __restrict__ topk_idx, int t_first, int nt, int k) {
+    const int ti = threadIdx.x >> 2;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ids[j] = (ti < nt && j < k) ? topk_idx[(size_t)(t_first + ti) * k + j] : -1;
+}
+
+// dL of the block's tokens, four lanes per token (lane `sub` takes experts sub, sub+4, ...; maxima and
+// sums are folded over the four lanes).  The LDS tile holds the logits on entry and dL on return, with
+// zeros in the rows of missing tokens and in columns E .. E16-1 (E16 = E rounded up to 16).  dL also
+// goes to global memory, and, if dLt is given, as two bfloat16 terms (hi + lo, 16 bits of mantissa)
+// to dLt[(e/16)*32 + e%16][token] and dLt[(e/16)*32 + 16 + e%16][token], rows of tp_pad tokens.
+__device__ __forceinline__ void gate_block_dl(
+    float (*tile)[DWG_LD], const float* sdw, const int (&ids)[8], float* __restrict__ dL,
+    bf16_t* __restrict__ dLt, int tp_pad, int t_first, int tl0, int nt, int E, int k, int renorm) {
+    const int ti = threadIdx.x >> 2, sub = threadIdx.x & 3;
+    const int E16 = (E + 15) & ~15;
+    const bool live = ti < nt;
+    const int t = t_first + ti;
+    float* row = tile[ti];
+    float mx = -INFINITY;
+    if (live)
+        for (int e = sub; e < E; e += 4) mx = fmaxf(mx, row[e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+    float g[8], pc[8];                  // gradient and exp(logit - max) of the chosen experts
+    float den = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        g[j] = 0.0f; pc[j] = 0.0f;
+        if (live && j < k) {
+            g[j] = sdw[ti * k + j];
+            pc[j] = expf(row[ids[j]] - mx);
+            den += pc[j];
+        }
+    }
+    if (!renorm) {
+        float sum = 0.0f;
+        if (live)
+            for (int e = sub; e < E; e += 4) sum += expf(row[e] - mx);
+        sum += __shfl_xor(sum, 1, 64);
+        sum += __shfl_xor(sum, 2, 64);
+        den = sum;
+    }
+    // (renormalised weights are a softmax over the chosen logits only: dL_e = w_j (dw_j - sum_j' dw_j' w_j')
+    // for a chosen e, zero otherwise)
+    const float inv = 1.0f / den;
+    float inner = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) inner = fmaf(g[j], pc[j] * inv, inner);
+    for (int e = sub; e < E16; e += 4) {
+        float v = 0.0f;
+        if (live && e < E) {
+            float dp = 0.0f;
+            bool chosen = false;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (ids[j] == e) { dp = g[j]; chosen = true; }
+            if (!renorm) v = expf(row[e] - mx) * inv * (dp - inner);
+            else if (chosen) v = expf(row[e] - mx) * inv * (dp - inner);
+            dL[(size_t)t * E + e] = v;
+        }
+        row[e] = v;
+        if (dLt) {
+            const bf16_t hi = f32_to_bf16(v);
+            const bf16_t lo = f32_to_bf16(v - bf16_to_f32(hi));
+            bf16_t* col = dLt + ((size_t)((e >> 4) * 32 + (e & 15)) * tp_pad + tl0 + ti);
+            col[0] = hi;
+            col[(size_t)16 * tp_pad] = lo;
+        }
+    }
+}
+
+// One workgroup takes DWG_TOK tokens: first dL of those tokens (to global memory for the
+// dispatch-backward kernel, and to LDS), then part[b][d][e] = sum over the tokens of
+// x[t,d] * dL[t,e] in float FMAs, each thread owning eight columns d.
+template <typename T>
+__global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
+    const T* __restrict__ x, const float* __restrict__ logits, const int* __restrict__ topk_idx,
+    const int* __restrict__ slot, const float* __restrict__ dw, const float* __restrict__ dw_part, int parts,
+    float* __restrict__ dL, float* __restrict__ part, int t_begin, int t_count, int M, int E, int k, int renorm) {
+    __shared__ __attribute__((aligned(16))) float sdl[DWG_TOK][DWG_LD];
+    __shared__ float sdw[DWG_TOK * 8];
+    const int tl0 = blockIdx.y * DWG_TOK;
+    const int nt = min(DWG_TOK, t_count - tl0);
+    int ids[8];
+    gate_block_ids(ids, topk_idx, t_begin + tl0, nt, k);
+    gate_block_logits(sdl, logits, t_begin + tl0, nt, E);
+    gate_block_dw(sdw, slot, dw, dw_part, parts, t_begin + tl0, nt, k);
     __syncthreads();
-    if ((int)threadIdx.x < nt)
-        gate_dl_token(logits, topk_idx, sdw + threadIdx.x * k, dL, sdl[threadIdx.x], t_begin + tl0 + threadIdx.x, E, k, renorm);
+    gate_block_dl(sdl, sdw, ids, dL, nullptr, 0, t_begin + tl0, tl0, nt, E, k, renorm);
     __syncthreads();
     for (int c = threadIdx.x * 8; c < M; c += PERM_THREADS * 8) {
         for (int e0 = 0; e0 < E; e0 += 16) {
@@ -587,35 +652,52 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
             for (int i = 0; i < 8; ++i)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
-            // the rows of the next four tokens are requested before the current four are used
-            // (tokens past the end are clamped here and get weight zero below)
-            Raw8<T> cur[4], nxt[4];
+            // Four token rows at a time, in two register sets in turn: the next four rows are
+            // requested before the current four are used, with no branch between request and use.
+            // Tokens past the end are clamped to the last one; their rows of sdl are zero.
+            auto request = [&](Raw8<T>* r, int i0) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) cur[u].load(x + (size_t)(t_begin + tl0 + min(u, nt - 1)) * M + c);
-            for (int i0 = 0; i0 < nt; i0 += 4) {
-                if (i0 + 4 < nt) {
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) nxt[u].load(x + (size_t)(t_begin + tl0 + min(i0 + 4 + u, nt - 1)) * M + c);
-                }
+                for (int u = 0; u < 4; ++u) r[u].load(x + (size_t)(t_begin + tl0 + min(i0 + u, nt - 1)) * M + c);
+            };
+            auto use = [&](const Raw8<T>* r, int i0) {
                 float xv[4][8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) cur[u].to_float(xv[u]);
+                for (int u = 0; u < 4; ++u) r[u].to_float(xv[u]);
+                // the gradients of token u+1 are read from LDS while token u is multiplied
+                float4 g4[2][4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) g4[0][v] = *reinterpret_cast<const float4*>(&sdl[i0][e0 + 4 * v]);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    float4 g4[4];
+                    if (u + 1 < 4) {
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) g4[v] = *reinterpret_cast<const float4*>(&sdl[i0 + u][e0 + 4 * v]);
+                        for (int v = 0; v < 4; ++v)
+                            g4[(u + 1) & 1][v] = *reinterpret_cast<const float4*>(&sdl[i0 + u + 1][e0 + 4 * v]);
+                    }
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const float gd[4] = {g4[v].x, g4[v].y, g4[v].z, g4[v].w};
+                        const float4 gq = g4[u & 1][v];
+                        const float gd[4] = {gq.x, gq.y, gq.z, gq.w};
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
+                        for (int r4 = 0; r4 < 4; ++r4)
 #pragma unroll
-                            for (int q = 0; q < 8; ++q) acc[q][4 * v + r] = fmaf(xv[u][q], gd[r], acc[q][4 * v + r]);
+                            for (int q = 0; q < 8; ++q) acc[q][4 * v + r4] = fmaf(xv[u][q], gd[r4], acc[q][4 * v + r4]);
                     }
                 }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
+            };
+            static_assert(DWG_TOK % 8 == 0, "the loop below walks over sdl in steps of eight rows");
+            Raw8<T> ca[4], cb[4];
+            request(ca, 0);
+            for (int i0 = 0; i0 < nt; i0 += 8) {
+                // (the barriers keep the instruction scheduler from sinking the requests to their uses)
+                request(cb, i0 + 4);
+                __builtin_amdgcn_sched_barrier(0);
+                use(ca, i0);
+                __builtin_amdgcn_sched_barrier(0);
+                request(ca, i0 + 8);
+                __builtin_amdgcn_sched_barrier(0);
+                use(cb, i0 + 4);
+                __builtin_amdgcn_sched_barrier(0);
             }
             float* out = part + ((size_t)blockIdx.y * M + c) * E + e0;
             if (ne == 16 && (E & 3) == 0) {
@@ -633,6 +715,139 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_bwd_kernel(
                         if (e < ne) out[(size_t)q * E + e] = acc[q][e];
             }
         }
+    }
+}
+
+
+// bfloat16 storage: dL of one block of tokens per workgroup, to global memory in float (for the
+// dispatch-backward kernel) and transposed as hi + lo bfloat16 terms (for the kernel below).
+__global__ __launch_bounds__(PERM_THREADS) void gate_dl_kernel(
+    const float* __restrict__ logits, const int* __restrict__ topk_idx, const int* __restrict__ slot,
+    const float* __restrict__ dw, const float* __restrict__ dw_part, int parts, float* __restrict__ dL,
+    bf16_t* __restrict__ dLt, int tp_pad, int t_begin, int t_count, int E, int k, int renorm) {
+    __shared__ __attribute__((aligned(16))) float sdl[DWG_TOK][DWG_LD];
+    __shared__ float sdw[DWG_TOK * 8];
+    const int tl0 = blockIdx.x * DWG_TOK;
+    const int nt = max(0, min(DWG_TOK, t_count - tl0));
+    int ids[8];
+    gate_block_ids(ids, topk_idx, t_begin + tl0, nt, k);
+    gate_block_logits(sdl, logits, t_begin + tl0, nt, E);
+    gate_block_dw(sdw, slot, dw, dw_part, parts, t_begin + tl0, nt, k);
+    __syncthreads();
+    gate_block_dl(sdl, sdw, ids, dL, dLt, tp_pad, t_begin + tl0, tl0, nt, E, k, renorm);
+}
+
+// part[s][d][e] = sum over the tokens of chunk s of x[t,d] * dL[t,e] on the matrix cores
+// (bfloat16 storage).  The tokens are the reduction dimension of v_mfma_f32_32x32x16_bf16, and
+// both operands want eight consecutive tokens in a lane: dL comes transposed from the kernel
+// above; of x a lane reads one dword (two neighbouring columns) from each of eight token rows
+// - every such read covers whole 128-byte lines of two rows - and splits them into the operand
+// of the even and of the odd columns.  A wavefront owns 64 columns and a chunk of TC tokens;
+// the first operand holds 32 columns of dL^T: sixteen experts' hi terms and their lo terms, so that
+// hi and lo products land in accumulator registers q and q + 8 of the same lane.
+// (The kernel is written for CPL = 2, 4 or 8 columns per lane; wider reads with fewer, fatter
+// wavefronts measured no faster - 26-29 us for gate backward of 16384 x 2048 in every shape - and
+// need more partial sums, so two it is.)
+constexpr int DWG_CPL = 2;
+typedef __bf16 gate_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float gate_f32x16 __attribute__((ext_vector_type(16)));
+template <int W> struct GateWords;            // W dwords of a token row
+template <> struct GateWords<1> { typedef unsigned type; static __device__ __forceinline__ unsigned word(const unsigned& v, int) { return v; } };
+template <> struct GateWords<2> { typedef uint2 type; static __device__ __forceinline__ unsigned word(const uint2& v, int i) { return i == 0 ? v.x : v.y; } };
+template <> struct GateWords<4> { typedef uint4 type; static __device__ __forceinline__ unsigned word(const uint4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; } };
+template <int EB, int CPL>           // expert blocks of sixteen: E <= 16*EB; columns per lane
+__global__ __launch_bounds__(PERM_THREADS) void gate_dwg_mfma_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ dLt, float* __restrict__ part,
+    int t_begin, int t_count, int tp_pad, int M, int E, int S, int TC) {
+    constexpr int U = (EB * CPL <= 4) ? 4 : 2;      // MFMA steps of 16 tokens requested together
+    constexpr int BT = 16 * U;
+    constexpr int W = CPL / 2;
+    typedef typename GateWords<W>::type row_t;
+    const int lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
+    const int ncb = (M + 32 * CPL - 1) / (32 * CPL);
+    const int w = blockIdx.x * PERM_WAVES + (threadIdx.x >> 6);
+    const int cb = w % ncb, s = w / ncb;
+    if (s >= S) return;
+    const int t0 = s * TC, t1 = min(t0 + TC, tp_pad);
+    const int c = cb * 32 * CPL + CPL * r;
+    const row_t* xcol = reinterpret_cast<const row_t*>(x + (size_t)t_begin * M + min(c, M - CPL));
+    const size_t row_units = (size_t)(M / CPL);
+    struct Blk { row_t xa[U][8]; uint4 b[U][EB]; };
+    // tokens past the partition are clamped to its last one (their dL is zero); a block past the
+    // chunk is requested from the last block of the buffer and never used
+    auto request = [&](Blk& q, int tb) {
+        tb = min(tb, tp_pad - BT);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                q.xa[u][j] = xcol[(size_t)min(tb + 16 * u + 8 * g + j, t_count - 1) * row_units];
+#pragma unroll
+            for (int eb = 0; eb < EB; ++eb)
+                q.b[u][eb] = *reinterpret_cast<const uint4*>(dLt + ((size_t)(eb * 32 + r) * tp_pad + tb + 16 * u + 8 * g));
+        }
+    };
+    gate_f32x16 acc[CPL][EB];
+#pragma unroll
+    for (int p = 0; p < CPL; ++p)
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[p][eb][q] = 0.0f;
+    auto use = [&](const Blk& q) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int p = 0; p < CPL; ++p) {
+                // column p of the lane over its eight tokens: the low or the high halves of word p/2
+                unsigned o[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const unsigned a = GateWords<W>::word(q.xa[u][2 * i], p >> 1), b2 = GateWords<W>::word(q.xa[u][2 * i + 1], p >> 1);
+                    o[i] = (p & 1) ? ((a >> 16) | (b2 & 0xffff0000u)) : ((a & 0xffffu) | (b2 << 16));
+                }
+                const gate_bf16x8 x8 = __builtin_bit_cast(gate_bf16x8, make_uint4(o[0], o[1], o[2], o[3]));
+#pragma unroll
+                for (int eb = 0; eb < EB; ++eb)
+                    acc[p][eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(gate_bf16x8, q.b[u][eb]), x8,
+                                                                         acc[p][eb], 0, 0, 0);
+            }
+    };
+    Blk ka, kb;
+    request(ka, t0);
+    for (int tb = t0; tb < t1; tb += 2 * BT) {
+        // (the barriers keep the instruction scheduler from sinking the requests to their uses)
+        request(kb, tb + BT);
+        __builtin_amdgcn_sched_barrier(0);
+        use(ka);
+        __builtin_amdgcn_sched_barrier(0);
+        request(ka, tb + 2 * BT);
+        __builtin_amdgcn_sched_barrier(0);
+        if (tb + BT < t1) use(kb);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // Accumulator register q of lane (r, g) belongs to column r of the x operand and to row
+    // 8*(q/4) + 4*g + q%4 of dL^T: rows 0-15 are the hi terms of sixteen experts, rows 16-31 their lo terms.
+    if (c >= M) return;
+#pragma unroll
+    for (int p = 0; p < CPL; ++p) {
+        float* out = part + ((size_t)s * M + c + p) * E;
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int e0 = 16 * eb + 8 * h + 4 * g;
+                float v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = acc[p][eb][4 * h + i] + acc[p][eb][4 * h + i + 8];
+                if ((E & 3) == 0) {
+                    if (e0 < E) *reinterpret_cast<float4*>(out + e0) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (e0 + i < E) out[e0 + i] = v[i];
+                }
+            }
     }
 }
 
@@ -676,16 +891,16 @@ template <typename T>
 static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const int* slot, const float* dL,
                                  const void* Wg, void* dx, hipStream_t s) {
     if (sizeof(T) == 2 && d.E <= 16) {      // more experts: the gate weights no longer fit a lane's registers
-        dim3 grid((d.M / 8 + PERM_THREADS - 1) / PERM_THREADS, (d.Tp + DXM_TOK * DXM_TG - 1) / (DXM_TOK * DXM_TG));
+        dim3 grid((d.M / 8 + DXM_CT - 1) / DXM_CT, (d.Tp + DXM_TOK * DXM_TG - 1) / (DXM_TOK * DXM_TG));
 #define LAUNCH_DXM(EG) do { \
-        const int lds = PERM_THREADS * (64 * EG + 16); \
+        const int lds = DXM_CT * (64 * EG + 16); \
         static bool attr_done = false; \
         if (!attr_done) { \
             HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(dispatch_bwd_mfma_kernel<EG>), \
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds)); \
             attr_done = true; \
         } \
-        hipLaunchKernelGGL((dispatch_bwd_mfma_kernel<EG>), grid, dim3(PERM_THREADS * DXM_TG), lds, s, \
+        hipLaunchKernelGGL((dispatch_bwd_mfma_kernel<EG>), grid, dim3(DXM_CT * DXM_TG), lds, s, \
         (const bf16_t*)dDI, slot, dL, (const bf16_t*)Wg, (bf16_t*)dx, part * d.Tp, d.Tp, d.M, d.E, d.k); } while (0)
         ProfScope ps(PK_DISPATCH_BWD, s);
         if (d.E <= 4) LAUNCH_DXM(1);
@@ -728,21 +943,63 @@ static moe_status dispatch_bwd_t(const Dims& d, int part, const void* dDI, const
     return MOE_OK;
 }
 
+// Shape of the bfloat16 gate-backward: token chunks of the matrix-core kernel and the two regions of
+// the scratch buffer (partial sums [S][M][E] float, then dL^T [EB*32][tp_pad] bfloat16).
+struct GateMfmaPlan { int tp_pad, EB, ncb, S, TC; size_t dlt_off, bytes; };
+static GateMfmaPlan gate_mfma_plan(const Dims& d) {
+    GateMfmaPlan g;
+    g.tp_pad = (d.Tp + DWG_TOK - 1) / DWG_TOK * DWG_TOK;
+    g.EB = (d.E + 15) / 16;
+    g.ncb = (d.M + 32 * DWG_CPL - 1) / (32 * DWG_CPL);
+    const int blocks = g.tp_pad / 64;
+    int S = 1024 / g.ncb;                     // about one wavefront per SIMD: more of them were slower
+    S = S < 1 ? 1 : (S > blocks ? blocks : S);
+    g.TC = (blocks + S - 1) / S * 64;
+    g.S = (g.tp_pad + g.TC - 1) / g.TC;
+    g.dlt_off = ((size_t)g.S * d.M * d.E * sizeof(float) + 255) / 256 * 256;
+    g.bytes = g.dlt_off + (size_t)g.EB * 32 * g.tp_pad * sizeof(bf16_t);
+    return g;
+}
+
+static void launch_dwg_reduce(const Dims& d, int part, const void* scratch, float* dWg, int nblk, hipStream_t s) {
+    const int ME = d.M * d.E;
+    hipLaunchKernelGGL(gate_dwg_reduce_kernel, dim3((ME + 31) / 32), dim3(256), 0, s,
+                       (const float*)scratch, dWg, nblk, ME, (d.overwrite && part == 0) ? 1 : 0);
+}
+
 template <typename T>
 static moe_status gate_bwd_t(const Dims& d, int part, const void* x, const float* logits, const int* idx,
                              const int* slot, const float* dw, const float* dw_part, int parts,
                              float* dL, float* dWg, void* scratch, hipStream_t s) {
     ProfScope ps(PK_GATE_BWD, s);
-    const int nblk = (d.Tp + DWG_TOK - 1) / DWG_TOK;
-    hipLaunchKernelGGL((gate_bwd_kernel<T>), dim3(1, nblk), dim3(PERM_THREADS), 0, s, (const T*)x, logits, idx,
-                       slot, dw, dw_part, parts, dL, (float*)scratch, part * d.Tp, d.Tp, d.M, d.E, d.k, d.renorm);
-    MOE_CHECK_LAUNCH();
-    const int ME = d.M * d.E;
-    hipLaunchKernelGGL(gate_dwg_reduce_kernel, dim3((ME + 31) / 32), dim3(256), 0, s,
-                       (const float*)scratch, dWg, nblk, ME, (d.overwrite && part == 0) ? 1 : 0);
-    count_launch(LC_OTHER, 2);
-    MOE_CHECK_LAUNCH();
-    return MOE_OK;
+    if constexpr (sizeof(T) == 2) {
+        const GateMfmaPlan g = gate_mfma_plan(d);
+        bf16_t* dLt = reinterpret_cast<bf16_t*>((char*)scratch + g.dlt_off);
+        hipLaunchKernelGGL(gate_dl_kernel, dim3(g.tp_pad / DWG_TOK), dim3(PERM_THREADS), 0, s, logits, idx, slot, dw,
+                           dw_part, parts, dL, dLt, g.tp_pad, part * d.Tp, d.Tp, d.E, d.k, d.renorm);
+        MOE_CHECK_LAUNCH();
+        const dim3 grid((g.ncb * g.S + PERM_WAVES - 1) / PERM_WAVES);
+#define LAUNCH_DWG(EB) hipLaunchKernelGGL((gate_dwg_mfma_kernel<EB, DWG_CPL>), grid, dim3(PERM_THREADS), 0, s, (const bf16_t*)x, \
+                           dLt, (float*)scratch, part * d.Tp, d.Tp, g.tp_pad, d.M, d.E, g.S, g.TC)
+        if (g.EB == 1) LAUNCH_DWG(1);
+        else if (g.EB == 2) LAUNCH_DWG(2);
+        else LAUNCH_DWG(4);
+#undef LAUNCH_DWG
+        MOE_CHECK_LAUNCH();
+        launch_dwg_reduce(d, part, scratch, dWg, g.S, s);
+        count_launch(LC_OTHER, 3);
+        MOE_CHECK_LAUNCH();
+        return MOE_OK;
+    } else {
+        const int nblk = (d.Tp + DWG_TOK - 1) / DWG_TOK;
+        hipLaunchKernelGGL((gate_bwd_kernel<T>), dim3(1, nblk), dim3(PERM_THREADS), 0, s, (const T*)x, logits, idx,
+                           slot, dw, dw_part, parts, dL, (float*)scratch, part * d.Tp, d.Tp, d.M, d.E, d.k, d.renorm);
+        MOE_CHECK_LAUNCH();
+        launch_dwg_reduce(d, part, scratch, dWg, nblk, s);
+        count_launch(LC_OTHER, 2);
+        MOE_CHECK_LAUNCH();
+        return MOE_OK;
+    }
 }
 
 }  // namespace moe
@@ -806,7 +1063,8 @@ extern "C" moe_status moe_gate_scratch_bytes(const moe_config* cfg, size_t* byte
     Dims d;
     MOE_TRY(make_dims(cfg, &d));
     if (!bytes) return MOE_ERR_NULL;
-    *bytes = (size_t)((d.Tp + DWG_TOK - 1) / DWG_TOK) * d.M * d.E * sizeof(float);
+    *bytes = d.dtype == MOE_BF16 ? gate_mfma_plan(d).bytes
+                                 : (size_t)((d.Tp + DWG_TOK - 1) / DWG_TOK) * d.M * d.E * sizeof(float);
     return MOE_OK;
 }
 
