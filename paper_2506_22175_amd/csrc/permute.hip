@@ -504,51 +504,77 @@ constexpr int DWG_LD = DWG_EMAX + 4;     // floats per row of the block's LDS ti
 
 // Combine-weight gradients of the block's (token, choice) pairs into sdw[ti*k + j]: either given,
 // or the fixed-order sum of the GEMM epilogue's column-block partial sums (four lanes per pair).
+// A thread has at most DWG_TOK*8*4/256 = 8 pairs; their slots are all requested before the first
+// row of partial sums is read.
 __device__ __forceinline__ void gate_block_dw(
     float* sdw, const int* __restrict__ slot, const float* __restrict__ dw, const float* __restrict__ dw_part,
     int parts, int t_first, int nt, int k) {
-    for (int q = threadIdx.x; q < nt * k * 4; q += PERM_THREADS) {
-        const int pair = q >> 2, sub = q & 3;
-        const int ti = pair / k, j = pair - ti * k;
-        const int t = t_first + ti;
-        float v = 0.0f;
-        if (dw_part) {
-            const int sl = slot[(size_t)t * k + j];
-            if (sl >= 0) {
-                const float* row = dw_part + (size_t)sl * parts;
-                if ((parts & 3) == 0) {
-                    // lane `sub` of the pair takes every fourth group of four partial sums, all
-                    // requested before the first is added (fixed order: groups ascending, then the lanes)
-                    const int ngrp = parts >> 2;
-                    for (int g0 = sub; g0 < ngrp; g0 += 32) {
-                        float4 q4[8];
+    constexpr int NI = DWG_TOK * 8 * 4 / PERM_THREADS;
+    const int total = nt * k * 4;
+    const int sub = threadIdx.x & 3;
+    int sl[NI];
+    float given[NI];
 #pragma unroll
-                        for (int u = 0; u < 8; ++u)
-                            q4[u] = (g0 + 4 * u < ngrp) ? *reinterpret_cast<const float4*>(row + 4 * (g0 + 4 * u))
-                                                        : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int i = 0; i < NI; ++i) {
+        const int q = threadIdx.x + i * PERM_THREADS;
+        const size_t at = (size_t)t_first * k + (q >> 2);          // pairs of the block are consecutive
+        sl[i] = (q < total && dw_part) ? slot[at] : -1;
+        given[i] = (q < total && !dw_part && sub == 0) ? dw[at] : 0.0f;
+    }
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) v += (q4[u].x + q4[u].y) + (q4[u].z + q4[u].w);
-                    }
-                } else {
-                    const int per = (parts + 3) >> 2;
-                    const int c1 = min(parts, (sub + 1) * per);
-                    for (int c = sub * per; c < c1; ++c) v += row[c];
+    for (int i = 0; i < NI; ++i) {
+        const int q = threadIdx.x + i * PERM_THREADS;
+        if (q >= total) break;                                     // uniform over the four lanes of a pair
+        float v = given[i];
+        if (sl[i] >= 0) {
+            const float* row = dw_part + (size_t)sl[i] * parts;
+            if ((parts & 3) == 0) {
+                // lane `sub` of the pair takes every fourth group of four partial sums, all
+                // requested before the first is added (fixed order: groups ascending, then the lanes)
+                const int ngrp = parts >> 2;
+                for (int g0 = sub; g0 < ngrp; g0 += 32) {
+                    float4 q4[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        q4[u] = (g0 + 4 * u < ngrp) ? *reinterpret_cast<const float4*>(row + 4 * (g0 + 4 * u))
+                                                    : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v += (q4[u].x + q4[u].y) + (q4[u].z + q4[u].w);
                 }
+            } else {
+                const int per = (parts + 3) >> 2;
+                const int c1 = min(parts, (sub + 1) * per);
+                for (int c = sub * per; c < c1; ++c) v += row[c];
             }
-        } else if (sub == 0) {
-            v = dw[(size_t)t * k + j];
         }
         v += __shfl_xor(v, 1, 64);
         v += __shfl_xor(v, 2, 64);
-        if (sub == 0) sdw[pair] = v;
+        if (sub == 0) sdw[q >> 2] = v;
     }
 }
 
-// The block's logits (nt rows of E floats, contiguous in memory) into the LDS tile.
+// The block's logits (nt rows of E floats, contiguous in memory) into the LDS tile; a thread's
+// loads (at most DWG_TOK*DWG_EMAX/256 = 16 floats) are all requested before the first is written.
 __device__ __forceinline__ void gate_block_logits(float (*tile)[DWG_LD], const float* __restrict__ logits,
                                                   int t_first, int nt, int E) {
     const float* src = logits + (size_t)t_first * E;
-    for (int q = threadIdx.x; q < nt * E; q += PERM_THREADS) tile[q / E][q % E] = src[q];
+    if ((E & 3) == 0 && (((size_t)t_first * E) & 3) == 0) {
+        constexpr int NI = DWG_TOK * DWG_EMAX / 4 / PERM_THREADS;
+        const int E4 = E >> 2, total = nt * E4;
+        float4 v[NI];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int q = threadIdx.x + i * PERM_THREADS;
+            v[i] = q < total ? reinterpret_cast<const float4*>(src)[q] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int q = threadIdx.x + i * PERM_THREADS;
+            if (q < total) *reinterpret_cast<float4*>(&tile[q / E4][4 * (q % E4)]) = v[i];
+        }
+    } else {
+        for (int q = threadIdx.x; q < nt * E; q += PERM_THREADS) tile[q / E][q % E] = src[q];
+    }
 }
 
 // The experts chosen by the token of this thread (thread / 4 within the block), -1 beyond k or past the

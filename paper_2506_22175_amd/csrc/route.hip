@@ -173,26 +173,42 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
             RowLoad<T>::load(r[tb], rs, (unsigned)(((size_t)tb * M + d0) * ES));
     };
 
-    // gate-weight rows c0 .. c0+MC-1 into LDS (whole workgroup; barriers before and after)
-    auto stage_weights = [&](int c0) __attribute__((always_inline)) {
+    // gate-weight rows c0 .. c0+MC-1 into LDS (whole workgroup; barriers before and after).
+    // between() runs after the weights have been requested and before they are written to LDS:
+    // an LDS write waits for every load issued before it, so the first token rows are requested there.
+    auto stage_weights = [&](int c0, auto&& between) __attribute__((always_inline)) {
         __syncthreads();
         // LDS element of (row dl, expert e): span = dl/512, lane l = (dl/8)%64, i = dl%8
         //   index = ((((span*8 + i) * E4 + e/4) * 64 + l) * 4 + e%4
         if (EP % 8 == 0 && E == EP && (reinterpret_cast<unsigned long long>(Wg) & 15ull) == 0) {
-            // eight experts of one row per load, several loads in flight per thread
+            // eight experts of one row per load; a thread's loads (at most eight: MC*EP <= 32768) are all
+            // in flight before the first is converted
             constexpr int G = EP / 8 > 0 ? EP / 8 : 1;
-#pragma unroll 8
-            for (int q = tid; q < MC * G; q += ROUTE_THREADS) {
-                const int dl = q / G, e0 = (q % G) * 8;
-                const int d = c0 + dl;
-                float v[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-                if (d < M) Vec8<T>::load(Wg + (size_t)d * E + e0, v);
-                const int span = dl >> 9, l = (dl >> 3) & 63, i = dl & 7;
-                float* dst = wl + ((((span * 8 + i) * E4 + (e0 >> 2)) * 64 + l) << 2);
-                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-                *reinterpret_cast<float4*>(dst + 256) = make_float4(v[4], v[5], v[6], v[7]);
+            constexpr int NP = 32768 / 8 / ROUTE_THREADS;
+            Raw8<T> wr[NP];
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int q = tid + i * ROUTE_THREADS;
+                const int d = c0 + q / G;
+                if (q < MC * G && d < M) wr[i].load(Wg + (size_t)d * E + (q % G) * 8);
+                else wr[i].zero();
+            }
+            between();
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int q = tid + i * ROUTE_THREADS;
+                if (q < MC * G) {
+                    const int dl = q / G, e0 = (q % G) * 8;
+                    float v[8];
+                    wr[i].to_float(v);
+                    const int span = dl >> 9, l = (dl >> 3) & 63, i8 = dl & 7;
+                    float* dst = wl + ((((span * 8 + i8) * E4 + (e0 >> 2)) * 64 + l) << 2);
+                    *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                    *reinterpret_cast<float4*>(dst + 256) = make_float4(v[4], v[5], v[6], v[7]);
+                }
             }
         } else {
+            between();
             for (int q = tid; q < MC * EP; q += ROUTE_THREADS) {
                 int dl = q / EP, e = q % EP;
                 int d = c0 + dl;
@@ -271,8 +287,7 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
             if (++rsp == nspan) { rsp = 0; rg += gridDim.x; }
         };
         Raw8<T> xa[TB], xb[TB];
-        request(xa);                                // in flight while the gate weights are staged
-        stage_weights(0);
+        stage_weights(0, [&]() __attribute__((always_inline)) { request(xa); });
         int g = blockIdx.x, sp = 0;                 // the span to multiply next
         auto multiply = [&](const Raw8<T>* cur) __attribute__((always_inline)) {
             if (sp * 512 + d_lane < M) multiply_span(acc, cur, sp);
@@ -300,7 +315,7 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
             const __amdgpu_buffer_rsrc_t rs = rows_of(g);
             for (int ch = 0; ch < nchunks; ++ch) {
                 const int c0 = ch * MC;
-                stage_weights(c0);
+                stage_weights(c0, []() {});
                 const int nspan = (min(MC, M - c0) + 511) / 512;
                 for (int sp = 0; sp < nspan; ++sp) {
                     const int d0 = c0 + sp * 512 + d_lane;

@@ -105,6 +105,9 @@ CASES = [
     # choices per token, a last round of two tokens; then an expert count that is no multiple of four
     ("wide_rows_k4_bf16", 102, 2304, 64, 16, 4, 1.0, "bf16", 1, None),
     ("wide_rows_odd_experts_bf16", 90, 2056, 40, 7, 3, 1.5, "bf16", 3, None),
+    # gate backward on the matrix cores: two blocks of sixteen experts with a ragged second block, columns
+    # that end inside a wavefront's 64, partitions that end inside a block of 64 tokens
+    ("gate_blocks_bf16", 260, 200, 64, 18, 2, 1.25, "bf16", 2, None),
 ]
 
 
