@@ -279,7 +279,7 @@ struct KCursor { int seg, jl, tiles; };
 // workgroup nor the first trip to memory stands between two main loops.
 template <int LAY, int EPI, typename C>
 __global__ __launch_bounds__(C::THREADS) __attribute__((amdgpu_waves_per_eu(C::OCC, C::OCC)))
-void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
+void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int BM = C::BM, BN = C::BN, WM = C::WM, WN = C::WN, TM = C::TM, TNN = C::TN;
     constexpr int STAGE = C::STAGE_BYTES, BK = C::BK, NS = C::NS;
@@ -315,6 +315,26 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     for (int j = 0; j < TNN; ++j) fb[j].init(wn * WN + j * 32, lane);
 
     // ---- tile number -> (expert, tile) -----------------------------------------------
+    // Only tiles that exist are numbered: an expert with fewer rows than the capacity has fewer
+    // tile rows (NN, NT), an expert without rows has no tiles at all (TN), so that the workgroups,
+    // which take the numbers b, b + grid, ..., all get the same amount of work whatever the spread
+    // of the counts.  Lane l of every wavefront holds the tiles of expert l (E <= 64); an inclusive
+    // scan over the lanes gives the number at which each expert ends.
+    int lane_tm = 0;                     // tile rows of expert `lane` (none: the expert has no tiles)
+    if (lane < g.E) {
+        int rows = 0;
+        const int segs = (LAY == GEMM_TN && g.k_segs > 1) ? g.k_segs : 1;
+        for (int sg = 0; sg < segs; ++sg) rows += g.counts[sg * g.E + lane];
+        if (LAY == GEMM_TN) lane_tm = (rows > 0 || EPI == EPI_STORE_F32) ? tiles_m : 0;   // a plain store still writes zeros
+        else lane_tm = min(tiles_m, (rows + BM - 1) / BM);
+    }
+    int lane_end = lane_tm * tiles_n;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(lane_end, off, 64);
+        if (lane >= off) lane_end += o;
+    }
+    const int nblocks = __builtin_amdgcn_readlane(lane_end, 63);
     // Tiles are numbered expert by expert, in groups of 4 tile-rows walked column by
     // column, so 32 consecutive numbers form a 4 x 8 block that shares 4 A panels and 8
     // B panels.  Hardware deals consecutive workgroup ids round-robin to the 8 XCDs (each
@@ -326,14 +346,15 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n, int nblocks) {
     // it is 3-5 % faster.)  A last partial run keeps plain order.
     auto decode = [&](int b, TileCoord& t) -> bool {
         const int lin = (b < (nblocks & ~255)) ? (b & ~255) + (b & 7) * 32 + ((b >> 3) & 31) : b;
-        const int per_e = tiles_m * tiles_n;
-        const int e = lin / per_e;
+        // the expert: as many experts end at or before lin as lanes say so (the ends never decrease)
+        const int e = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane_end <= lin));
         if (e >= g.E) return false;
-        const int rem = lin - e * per_e;
+        const int tm_e = __builtin_amdgcn_readlane(lane_tm, e);      // tile rows of this expert
+        const int rem = lin - (__builtin_amdgcn_readlane(lane_end, e) - tm_e * tiles_n);
         constexpr int GM = 4;
         const int grp = rem / (GM * tiles_n);
         const int first = grp * GM;
-        const int gsz = min(GM, tiles_m - first);
+        const int gsz = min(GM, tm_e - first);
         const int in = rem - grp * GM * tiles_n;
         const int tm = first + in % gsz;
         t.tn = in / gsz;
@@ -855,7 +876,7 @@ static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
     }
     {
         ProfScope ps(gemm_prof_kind(LAY, EPI), s);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(C::THREADS), lds, s, a, tiles_m, tiles_n, nblocks);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(C::THREADS), lds, s, a, tiles_m, tiles_n);
     }
     count_launch(LC_GEMM);
     MOE_CHECK_LAUNCH();
