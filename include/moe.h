@@ -208,7 +208,9 @@ moe_status moe_combine(const moe_config* cfg, int32_t part, const void* DO, cons
 
 /* Gate backward of partition `part`: dL = softmax Jacobian applied to the
  * combine-weight gradients, dWg += x^T dL (two-stage, fixed order; dWg = x^T dL
- * when cfg->grad_overwrite and part == 0).
+ * when cfg->grad_overwrite and part == 0).  float32 storage multiplies in float;
+ * bfloat16 storage multiplies on the matrix cores with dL split into two bfloat16
+ * terms (16 bits of mantissa) and float accumulation.
  *   dw [T,k] float (used when dw_part is NULL) or dw_part [R_p, parts] summed in
  *   ascending c; dL [T,E] float out; scratch: moe_gate_scratch_bytes(cfg). */
 moe_status moe_gate_bwd(const moe_config* cfg, int32_t part, const void* x, const float* logits,
