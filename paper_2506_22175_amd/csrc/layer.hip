@@ -100,10 +100,41 @@ static moe_status get_events(size_t n) {
     return MOE_OK;
 }
 
+// R'_p: the rows of dy of partition p to the experts (and, where forward kept no T_DI buffer for it, the
+// rows of x again); with T_DO kept, the combine-weight gradients <dy_t, T_DO row> on the way.
+static moe_status dispatch_for_backward(const moe_config* cfg, const Dims& d, const Workspace& w, char* ws, int p,
+                                        const void* x, const void* dy, const int* slot, bool redispatch,
+                                        bool dw_in_gemm, hipStream_t s0) {
+    char* DI = ws + w.DI + w.bufM * (p % w.nDI);
+    char* DO = w.nDO ? ws + w.DO + w.bufM * (p % w.nDO) : nullptr;
+    char* dDO = ws + w.dDO + w.bufM * (p % w.ndDO);
+    if (dw_in_gemm) {
+        MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDO, nullptr, nullptr, s0));
+        if (redispatch) MOE_TRY(moe_dispatch(cfg, p, x, slot, DI, nullptr, nullptr, s0));
+    } else {
+        // T_DO was kept: the combine-weight gradient is <dy_t, T_DO row>
+        MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDO, DO, (float*)(ws + w.dw), s0));
+        if (d.fuse) MOE_TRY(moe_dispatch(cfg, p, x, slot, DI, nullptr, nullptr, s0));
+    }
+    return MOE_OK;
+}
+
+// In a whole step R'_0 need not wait for the end of forward: what it writes (the first dT_DO buffer, the first
+// T_DI buffer when x is dispatched again) was last touched by partitions before the last one, unless the last
+// partition shares those buffers.  It is then queued on stream 0 ahead of the last combine, so that the first
+// backward GEMM follows the last forward GEMM without a gap.
+static bool first_backward_dispatch_can_go_early(const Dims& d, const Workspace& w, bool offload) {
+    if (d.n < 2 || offload) return false;
+    const bool redispatch = w.nDI < d.n || d.fuse;
+    if (w.dDO_aliases_DO && (d.n - 1) % w.nDO == 0) return false;
+    if (redispatch && !d.fuse && (d.n - 1) % w.nDI == 0) return false;
+    return true;
+}
+
 static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace& w, char* ws,
                           const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* W2,
                           void* y, float* logits, int* topk_idx, float* topk_w, int* slot, int* counts,
-                          hipStream_t s0, hipStream_t s1, const Offload* off = nullptr) {
+                          hipStream_t s0, hipStream_t s1, const Offload* off = nullptr, const void* dy_early = nullptr) {
     const int n = d.n;
     MOE_TRY(get_events(7 * (size_t)n + 2));
     hipEvent_t* evS = g_events.data();
@@ -162,6 +193,13 @@ static moe_status forward(const moe_config* cfg, const Dims& d, const Workspace&
         if (p >= 1) {
             // R_{p-1}, issued after S_p so that S and R alternate on stream 0 (with the fused combine
             // C_{p-1} has written y itself and stream 0 only waits for it)
+            if (p == n && dy_early) {
+                // whole step: R'_0 of backward goes first (see first_backward_dispatch_can_go_early); backward
+                // finds its event recorded
+                const bool reuse = d.reuse != MOE_REUSE_NONE;
+                MOE_TRY(dispatch_for_backward(cfg, d, w, ws, 0, x, dy_early, slot, w.nDI < n || d.fuse, reuse || d.fcomb, s0));
+                HIP_TRY(hipEventRecord(evS[0], s0));
+            }
             HIP_TRY(hipStreamWaitEvent(s0, evC[p - 1], 0));
             if (!d.fcomb) MOE_TRY(moe_combine(cfg, p - 1, DObuf(p - 1), slot, topk_w, y, s0));
             HIP_TRY(hipEventRecord(evR[p - 1], s0));
@@ -178,7 +216,7 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
                            const void* x, const void* dy, const void* Wg, const void* W1, const void* W2,
                            void* dx, float* dWg, float* dW1, float* dW2,
                            const float* logits, const int* topk_idx, const int* slot, const int* counts,
-                           hipStream_t s0, hipStream_t s1, const Offload* off = nullptr) {
+                           hipStream_t s0, hipStream_t s1, const Offload* off = nullptr, bool first_dispatch_done = false) {
     const int n = d.n, G = d.G;
     MOE_TRY(get_events(7 * (size_t)n + 2));
     hipEvent_t* evS = g_events.data();        // R'_p done (rows of dy, and of x again, are in place)
@@ -208,26 +246,23 @@ static moe_status backward(const moe_config* cfg, const Dims& d, const Workspace
     const bool redispatch = !off_di && (w.nDI < n || d.fuse);
 
     HIP_TRY(hipEventRecord(evFork, s0));
-    HIP_TRY(hipStreamWaitEvent(s1, evFork, 0));
+    // (whole step with R'_0 already queued: the GEMM stream goes straight on from forward's last GEMM; what its
+    // first backward GEMMs touch is ordered by R'_0's event and by the stream itself)
+    if (!first_dispatch_done) HIP_TRY(hipStreamWaitEvent(s1, evFork, 0));
     // copies back into the shared buffers must not overtake the forward GEMMs that still read them
     if (off_di || off_z) HIP_TRY(hipStreamWaitEvent(off->s2, evFork, 0));
 
     for (int p = 0; p <= n; ++p) {
-        if (p < n) {
+        if (p < n && !(p == 0 && first_dispatch_done)) {
             // R'_p: rows of dy to the experts.  Their buffer (and the re-dispatched T_DI buffer) was last
             // read by partition p - (number of buffers): by its GEMMs and by the weight-gradient GEMMs of
             // its group, which come last.
             if (p >= w.ndDO) HIP_TRY(hipStreamWaitEvent(s0, evW[(p - w.ndDO) / G], 0));
             if (redispatch && p >= w.nDI && w.nDI != w.ndDO) HIP_TRY(hipStreamWaitEvent(s0, evW[(p - w.nDI) / G], 0));
-            if (dw_in_gemm) {
-                MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), nullptr, nullptr, s0));
-                if (redispatch) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
-            } else {
-                // T_DO was kept: the combine-weight gradient is <dy_t, T_DO row>
-                MOE_TRY(moe_dispatch(cfg, p, dy, slot, dDObuf(p), DObuf(p), dw, s0));
-                if (d.fuse) MOE_TRY(moe_dispatch(cfg, p, x, slot, DIbuf(p), nullptr, nullptr, s0));
-            }
+            MOE_TRY(dispatch_for_backward(cfg, d, w, ws, p, x, dy, slot, redispatch, dw_in_gemm, s0));
             HIP_TRY(hipEventRecord(evS[p], s0));
+        }
+        if (p < n) {
             if (off_di || off_z) {
                 // what was offloaded comes back into the shared buffers, last read by the GEMMs of p-2
                 // (the copy stream runs in order, so the forward copies are through)
@@ -338,10 +373,11 @@ extern "C" moe_status moe_layer_step(const moe_config* cfg, const void* x, const
     MOE_TRY(setup(cfg, &d, &w, workspace, workspace_bytes, streams, n_streams, &s0, &s1));
     if (!x || !dy || !Wg || !W1 || !W2 || !y || !dx || !dWg || !dW1 || !dW2 || !logits || !topk_idx ||
         !topk_w || !slot || !counts) return MOE_ERR_NULL;
+    const bool early = first_backward_dispatch_can_go_early(d, w, false);
     MOE_TRY(forward(cfg, d, w, (char*)workspace, x, Wg, gate_bias, W1, W2, y, logits, topk_idx, topk_w, slot,
-                    counts, s0, s1));
+                    counts, s0, s1, nullptr, early ? dy : nullptr));
     return backward(cfg, d, w, (char*)workspace, x, dy, Wg, W1, W2, dx, dWg, dW1, dW2, logits, topk_idx, slot,
-                    counts, s0, s1);
+                    counts, s0, s1, nullptr, early);
 }
 
 static void offload_layout(const Dims& d, const Workspace& w, Offload* o, size_t* total) {
