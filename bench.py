@@ -380,6 +380,15 @@ def main():
                 continue
             o, _, _ = measure(args, wl, n, mode, 5, 2, brief=True, group=grp)
             others.append(o)
+        # mid-size workload: every partition count under the three on-device memory modes (speed and
+        # workspace side by side: Section III-C's granularity against Section III-D's reuse)
+        grid = []
+        for n in (1, 2, 4, 8):
+            for mode in (0, 1, 2):
+                o, _, _ = measure(args, "gpt", n, mode, 5, 2, brief=True)
+                grid.append({k_: o[k_] for k_ in ("n_partitions", "reuse_mode", "ms_per_step", "tokens_per_s",
+                                                   "gemm_frac_of_peak", "workspace_bytes")})
+        out["gpt_partitions_by_mode"] = grid
         # the same configuration with the other setting of the gathered first GEMM
         o, _, _ = measure(args, args.workload, args.n, args.reuse, 10, 3, brief=True, fuse=0 if args.fuse_gather else 1)
         out["gathered_first_gemm"] = {"this_run": int(args.fuse_gather), "other_setting": o}
