@@ -686,6 +686,19 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n) {
             oC = in ? (unsigned)(m * g.ldc + n) * CES : OOB_OFFSET;
             oZ = in ? (unsigned)(m * g.ldz + n) * 2u : OOB_OFFSET;
         };
+        // Float outputs: a lane's two 16-byte halves of "piece" t are units 2t and 2t+1 of a numbering in which the
+        // 64 lanes of one store (or load) cover whole rows of the pass - 4 columns per lane, CW/4 lanes per row - so
+        // that every such instruction moves whole 128-byte lines (8 columns per lane would leave each instruction
+        // with every other 16 bytes).  Unit u of a lane is UROWS*u rows below its unit 0, in the same columns: one
+        // vector offset per pass, the rest is a scalar offset.
+        constexpr int ULANES = CW / 4, UROWS = 64 / ULANES;
+        const int urow = lane / ULANES, uc4 = lane % ULANES;
+        auto unit0 = [&](int ps) -> unsigned {
+            const int m = m0 + wm * WM + (ps / NCH) * 32 + urow;
+            const int n = n0 + wn * WN + (ps % NCH) * CW + uc4 * 4;
+            return n < g.N ? (unsigned)(m * g.ldc + n) * 4u : OOB_OFFSET;
+        };
+        const unsigned ustep = (unsigned)(UROWS * g.ldc) * 4u;      // bytes from one unit of a lane to the next
         auto request_pass = [&](int ps, PassIn& in) {
 #pragma unroll
             for (int t = 0; t < NPIECE; ++t) {
@@ -700,8 +713,9 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n) {
                     in.wrow[t] = m < Mdim ? wbase[m] : 0.0f;
                 }
                 if constexpr (EPI == EPI_ACCUM_F32) {
-                    in.cin0[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, oC, 0, 0));
-                    in.cin1[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, oC + 16u, 0, 0));
+                    const unsigned ob = unit0(ps);
+                    in.cin0[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, ob, (2 * t) * ustep, 0));
+                    in.cin1[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rC, ob, (2 * t + 1) * ustep, 0));
                 }
             }
         };
@@ -728,10 +742,16 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n) {
             constexpr bool HOIST = EPI != EPI_ACCUM_F32;
             float4 lo[NPIECE], hi[NPIECE];
             auto read_piece = [&](int t) {
-                const int idx = lane + 64 * t;
-                const int row = idx / CPRW, c8 = idx % CPRW;
-                lo[t] = *reinterpret_cast<const float4*>(stage + row * CW + (((2 * c8) ^ (row & 15)) << 2));
-                hi[t] = *reinterpret_cast<const float4*>(stage + row * CW + (((2 * c8 + 1) ^ (row & 15)) << 2));
+                if constexpr (CES == 4) {
+                    const int r0 = urow + UROWS * (2 * t), r1 = r0 + UROWS;
+                    lo[t] = *reinterpret_cast<const float4*>(stage + r0 * CW + ((uc4 ^ (r0 & 15)) << 2));
+                    hi[t] = *reinterpret_cast<const float4*>(stage + r1 * CW + ((uc4 ^ (r1 & 15)) << 2));
+                } else {
+                    const int idx = lane + 64 * t;
+                    const int row = idx / CPRW, c8 = idx % CPRW;
+                    lo[t] = *reinterpret_cast<const float4*>(stage + row * CW + (((2 * c8) ^ (row & 15)) << 2));
+                    hi[t] = *reinterpret_cast<const float4*>(stage + row * CW + (((2 * c8 + 1) ^ (row & 15)) << 2));
+                }
             };
             if constexpr (HOIST) {
 #pragma unroll
@@ -790,14 +810,16 @@ void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n) {
                             g.dw_part[((size_t)e * g.Cp + m) * g.dw_parts + tn * C::WAVES_N + wn] = dot;
                     }
                 } else if constexpr (EPI == EPI_STORE_F32) {
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, lo[t]), rC, oC, 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, hi[t]), rC, oC + 16u, 0, 0);
+                    const unsigned ob = unit0(ps);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, lo[t]), rC, ob, (2 * t) * ustep, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, hi[t]), rC, ob, (2 * t + 1) * ustep, 0);
                 } else {
+                    const unsigned ob = unit0(ps);
                     float4 o0 = in.cin0[t], o1 = in.cin1[t];
                     o0.x += v[0]; o0.y += v[1]; o0.z += v[2]; o0.w += v[3];
                     o1.x += v[4]; o1.y += v[5]; o1.z += v[6]; o1.w += v[7];
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o0), rC, oC, 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o1), rC, oC + 16u, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o0), rC, ob, (2 * t) * ustep, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, o1), rC, ob, (2 * t + 1) * ustep, 0);
                 }
             }
             // the next tile's first operand tiles start their trip once the first pass is through
@@ -883,17 +905,12 @@ static moe_status launch_one(const GemmArgs& a, hipStream_t s) {
     return MOE_OK;
 }
 
-template <int LAY>
-static moe_status launch_lay(GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
-    switch (epi) {
-        case EPI_STORE: return launch_one<LAY, EPI_STORE, typename CfgFor<LAY, EPI_STORE>::type>(a, s);
-        case EPI_GELU: return launch_one<LAY, EPI_GELU, typename CfgFor<LAY, EPI_GELU>::type>(a, s);
-        case EPI_DGELU: return launch_one<LAY, EPI_DGELU, typename CfgFor<LAY, EPI_DGELU>::type>(a, s);
-        case EPI_ACCUM_F32: return launch_one<LAY, EPI_ACCUM_F32, typename CfgFor<LAY, EPI_ACCUM_F32>::type>(a, s);
-        case EPI_STORE_F32: return launch_one<LAY, EPI_STORE_F32, typename CfgFor<LAY, EPI_STORE_F32>::type>(a, s);
-        case EPI_SCATTER: return launch_one<LAY, EPI_SCATTER, typename CfgFor<LAY, EPI_SCATTER>::type>(a, s);
-    }
-    return MOE_ERR_UNSUPPORTED;
+// Only the combinations the expert FFN uses are instantiated: NN with plain, GeLU and scattered stores
+// (both layers of forward, recomputation), NT with GeLU-backward and plain stores (the two input
+// gradients), TN with float store and float accumulation (the weight gradients).
+template <int LAY, int EPI>
+static moe_status launch_cfg(const GemmArgs& a, hipStream_t s) {
+    return launch_one<LAY, EPI, typename CfgFor<LAY, EPI>::type>(a, s);
 }
 
 }  // namespace moe
@@ -916,9 +933,14 @@ moe_status gemm_bf16(GemmLayout lay, GemmEpilogue epi, const GemmArgs& a, hipStr
         if (lay == GEMM_TN || a.a_row_limit <= 0) return MOE_ERR_UNSUPPORTED;
         if (((long long)a.a_row_limit + 1) * a.lda * 2 >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
     }
-    if (lay == GEMM_NN) return launch_lay<GEMM_NN>(epi, a, s);
-    if (lay == GEMM_NT) return launch_lay<GEMM_NT>(epi, a, s);
-    return launch_lay<GEMM_TN>(epi, a, s);
+    if (lay == GEMM_NN && epi == EPI_STORE) return launch_cfg<GEMM_NN, EPI_STORE>(a, s);
+    if (lay == GEMM_NN && epi == EPI_GELU) return launch_cfg<GEMM_NN, EPI_GELU>(a, s);
+    if (lay == GEMM_NN && epi == EPI_SCATTER) return launch_cfg<GEMM_NN, EPI_SCATTER>(a, s);
+    if (lay == GEMM_NT && epi == EPI_STORE) return launch_cfg<GEMM_NT, EPI_STORE>(a, s);
+    if (lay == GEMM_NT && epi == EPI_DGELU) return launch_cfg<GEMM_NT, EPI_DGELU>(a, s);
+    if (lay == GEMM_TN && epi == EPI_STORE_F32) return launch_cfg<GEMM_TN, EPI_STORE_F32>(a, s);
+    if (lay == GEMM_TN && epi == EPI_ACCUM_F32) return launch_cfg<GEMM_TN, EPI_ACCUM_F32>(a, s);
+    return MOE_ERR_UNSUPPORTED;
 }
 
 }  // namespace moe
